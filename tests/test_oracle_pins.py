@@ -1,0 +1,434 @@
+"""Pins for the CPU oracle: each checks oracle/psa_oracle.py against something the paper or the
+mathematics fixes, never against the oracle's own formula retyped.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import psa_oracle as orc
+from oracle.psa_oracle import Params
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---------------------------------------------------------------- Eq. 1: dense attention
+def _brute_dense(Q, K, V, scale, causal, group):
+    """Element-by-element softmax attention with python loops (tiny sizes only)."""
+    B, Hq, N, d = Q.shape
+    O = np.zeros_like(Q)
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // group
+            for r in range(N):
+                ws, acc = [], np.zeros(d)
+                for c in range(N):
+                    if causal and c > r:
+                        ws.append(0.0)
+                        continue
+                    dot = 0.0
+                    for x in range(d):
+                        dot += Q[b, h, r, x] * K[b, hk, c, x]
+                    ws.append(math.exp(dot * scale))
+                tot = sum(ws)
+                for c in range(N):
+                    acc += ws[c] / tot * V[b, hk, c]
+                O[b, h, r] = acc
+    return O
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_dense_matches_brute_force(causal):
+    B, Hq, Hkv, N, d = 1, 4, 2, 13, 4
+    Q, K, V = _rand(1, B, Hq, N, d), _rand(2, B, Hkv, N, d), _rand(3, B, Hkv, N, d)
+    p = Params(B, Hq, Hkv, N, d, bq=4, bk=4, levels=1, causal=causal)
+    O, lse = orc.dense_attention(Q, K, V, p)
+    ref = _brute_dense(Q, K, V, p.sm_scale, causal, Hq // Hkv)
+    np.testing.assert_allclose(O, ref, rtol=1e-12, atol=1e-12)
+    # lse is the log of the softmax denominator
+    s = (Q[0, 1] @ K[0, 0].T) * p.sm_scale
+    if causal:
+        s = np.where(np.arange(N)[None] > np.arange(N)[:, None], -np.inf, s)
+    np.testing.assert_allclose(lse[0, 1], np.log(np.exp(s).sum(1)), rtol=1e-12)
+
+
+def test_scale_default_is_inverse_sqrt_d():
+    p = Params(1, 1, 1, 8, 16, 4, 4, 1)
+    assert abs(p.sm_scale - 0.25) < 1e-7
+    assert abs(Params(1, 1, 1, 8, 16, 4, 4, 1, scale=0.5).sm_scale - 0.5) < 1e-7
+
+
+# ---------------------------------------------------------------- Eq. 2-3: pyramid
+def test_pyramid_equals_recursive_meanpool():
+    p = Params(1, 2, 2, 64, 8, bq=16, bk=16, levels=4, dtype="f32")
+    # small integers: every mean is exact in fp32, so recursion and direct mean agree bit for bit
+    X = np.random.default_rng(0).integers(-8, 9, size=(1, 2, 64, 8)).astype(np.float64) * 8.0
+    pyr = orc.build_pyramid(X, p)
+    level = X
+    for h in range(2, 5):
+        level = 0.5 * (level[:, :, 0::2] + level[:, :, 1::2])      # MeanPool(x, 2, 2)
+        assert pyr[h].shape == (1, 2, 64 >> (h - 1), 8)
+        np.testing.assert_array_equal(pyr[h], level)
+
+
+def test_pyramid_random_close_to_recursion_and_rounded_once():
+    p = Params(1, 1, 1, 128, 16, bq=32, bk=32, levels=4, dtype="bf16")
+    X = orc.round_store(_rand(5, 1, 1, 128, 16), "bf16")
+    pyr = orc.build_pyramid(X, p)
+    level = X
+    for h in range(2, 5):
+        level = 0.5 * (level[:, :, 0::2] + level[:, :, 1::2])
+        # one bf16 rounding of the exact mean: relative error at most 2^-9
+        assert np.all(np.abs(pyr[h] - level) <= np.abs(level) * 2.0 ** -8 + 1e-30)
+        # stored values are bf16-representable
+        np.testing.assert_array_equal(pyr[h], orc.round_store(pyr[h], "bf16"))
+
+
+def test_pyramid_constant_block_is_lossless():
+    p = Params(1, 1, 1, 64, 4, bq=16, bk=16, levels=4, dtype="bf16")
+    vals = orc.round_store(_rand(7, 4, 4), "bf16")                   # one vector per block
+    X = np.repeat(vals, 16, axis=0)[None, None]
+    pyr = orc.build_pyramid(X, p)
+    for h in range(2, 5):
+        t = 16 >> (h - 1)
+        np.testing.assert_array_equal(pyr[h][0, 0], np.repeat(vals, t, axis=0))
+
+
+def test_pyramid_ragged_tail_counts():
+    p = Params(1, 1, 1, 21, 2, bq=8, bk=8, levels=3, dtype="f32")    # 3 blocks, last has 5 tokens
+    X = np.arange(21 * 2, dtype=np.float64).reshape(1, 1, 21, 2)
+    pyr = orc.build_pyramid(X, p)
+    assert pyr[3].shape[2] == 6
+    np.testing.assert_array_equal(orc.pooled_counts(p, 3), [4, 4, 4, 4, 4, 1])
+    np.testing.assert_allclose(pyr[3][0, 0, 5], X[0, 0, 20])         # lone valid token
+    np.testing.assert_allclose(pyr[2][0, 0, 10], X[0, 0, 20])
+    np.testing.assert_array_equal(pyr[2][0, 0, 11], 0.0)              # covers nothing
+
+
+# ---------------------------------------------------------------- Alg. 1 / Eq. 8: PSA attention
+def _setup(seed, N=96, d=8, bq=16, bk=16, H=3, Hq=2, Hkv=1, causal=False, dtype="f32"):
+    p = Params(1, Hq, Hkv, N, d, bq, bk, H, dtype=dtype, causal=causal)
+    Q = orc.round_store(_rand(seed, 1, Hq, N, d), dtype)
+    K = orc.round_store(_rand(seed + 1, 1, Hkv, N, d), dtype)
+    V = orc.round_store(_rand(seed + 2, 1, Hkv, N, d), dtype)
+    return p, Q, K, V
+
+
+@pytest.mark.parametrize("N,causal", [(96, False), (90, False), (96, True), (83, True)])
+def test_all_level1_equals_dense(N, causal):
+    p, Q, K, V = _setup(10, N=N, causal=causal)
+    M = np.ones((1, p.Hq, p.nq, p.nk), dtype=np.uint8)
+    if causal:
+        M *= (orc.block_visibility(p) > 0)[None, None].astype(np.uint8)
+    O, lse = orc.psa_attention(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, p)
+    Od, lsed = orc.dense_attention(Q, K, V, p)
+    np.testing.assert_allclose(O, Od, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(lse, lsed, rtol=1e-11, atol=1e-12)
+
+
+def _masked_dense(Q, K, V, M, p):
+    """Dense attention with -inf on the tokens of dropped blocks (brute-force block-sparse)."""
+    keep_tok = np.repeat(M > 0, p.bk, axis=-1)[..., :p.N]             # [B,Hq,nq,N]
+    O = np.zeros_like(Q)
+    for h in range(p.Hq):
+        hk = h // (p.Hq // p.Hkv)
+        for r in range(p.N):
+            s = (K[0, hk] @ Q[0, h, r]) * p.sm_scale
+            s = np.where(keep_tok[0, h, r // p.bq], s, -np.inf)
+            w = np.exp(s - s.max())
+            O[0, h, r] = (w / w.sum()) @ V[0, hk]
+    return O
+
+
+@pytest.mark.parametrize("N", [128, 116])
+def test_group_constant_keys_make_pooling_exact(N):
+    """If the keys inside every pooling group are identical, c*exp(q.kbar) = sum_t exp(q.k_t) and the
+    pooled value times c equals the sum of values, so PSA at ANY level equals dense attention over
+    the kept blocks.  A missing, doubled or wrongly signed (h-1) ln 2 breaks this."""
+    H = 4
+    p, Q, K, V = _setup(20, N=N, d=8, bq=16, bk=32, H=H, dtype="f32")
+    g = 1 << (H - 1)
+    Kc = np.repeat(K[:, :, ::g], g, axis=2)[:, :, :N]                 # constant over groups of 8
+    rng = np.random.default_rng(3)
+    M = rng.integers(0, H + 1, size=(1, p.Hq, p.nq, p.nk)).astype(np.uint8)
+    M[..., 0] = 1
+    O, _ = orc.psa_attention(Q, orc.build_pyramid(Kc, p), orc.build_pyramid(V, p), M, p)
+    ref = _masked_dense(Q, Kc, V, M, p)
+    # values are pooled through an fp32-rounded pyramid: 1e-6 relative
+    np.testing.assert_allclose(O, ref, rtol=0, atol=5e-6)
+    # identical keys AND values in a block (the lossless case): same statement, tighter
+    Vc = np.repeat(V[:, :, ::g], g, axis=2)[:, :, :N]
+    O2, _ = orc.psa_attention(Q, orc.build_pyramid(Kc, p), orc.build_pyramid(Vc, p), M, p)
+    np.testing.assert_allclose(O2, _masked_dense(Q, Kc, Vc, M, p), rtol=0, atol=1e-9)
+
+
+def test_wrong_bias_would_be_caught():
+    """Sensitivity of the pin above: the same comparison with the bias removed is far outside it."""
+    H = 3
+    p, Q, K, V = _setup(21, N=64, d=8, bq=16, bk=16, H=H)
+    Kc = np.repeat(K[:, :, ::4], 4, axis=2)
+    M = np.full((1, p.Hq, p.nq, p.nk), 3, dtype=np.uint8)
+    M[..., ::2] = 1
+    Kp, Vp = orc.build_pyramid(Kc, p), orc.build_pyramid(V, p)
+    O, _ = orc.psa_attention(Q, Kp, Vp, M, p)
+    # emulate "no bias": un-pooled weighting equals giving each pooled key weight 1 instead of 4
+    keep = _masked_dense(Q, Kc, V, M, p)
+    assert np.abs(O - keep).max() < 5e-6
+    nobias = np.zeros_like(O)
+    for h in range(p.Hq):
+        for r in range(p.N):
+            logits, vals = [], []
+            for j in range(p.nk):
+                lv = int(M[0, h, r // p.bq, j])
+                t = p.bk >> (lv - 1)
+                logits.append((Kp[lv][0, 0, j * t:(j + 1) * t] @ Q[0, h, r]) * p.sm_scale)
+                vals.append(Vp[lv][0, 0, j * t:(j + 1) * t])
+            s, v = np.concatenate(logits), np.concatenate(vals)
+            w = np.exp(s - s.max())
+            nobias[0, h, r] = (w / w.sum()) @ v
+    assert np.abs(nobias - keep).max() > 1e-2
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_online_recurrence_equals_closed_form(causal):
+    p, Q, K, V = _setup(30, N=120, d=8, bq=16, bk=16, H=4, causal=causal, dtype="bf16")
+    rng = np.random.default_rng(9)
+    M = rng.integers(0, 5, size=(1, p.Hq, p.nq, p.nk)).astype(np.uint8)
+    vis = orc.block_visibility(p)
+    M = np.where(vis[None, None] == 0, 0, M)
+    M = np.where(vis[None, None] == 2, 1, M).astype(np.uint8)
+    M[..., 0] = 1
+    Kp, Vp = orc.build_pyramid(K, p), orc.build_pyramid(V, p)
+    O, _ = orc.psa_attention(Q, Kp, Vp, M, p)
+    for h in range(p.Hq):
+        for i in range(p.nq):
+            cf = orc.psa_attention_closed_form(Q, Kp, Vp, M, p, 0, h, i)
+            np.testing.assert_allclose(O[0, h, i * p.bq:(i + 1) * p.bq], cf, rtol=1e-11, atol=1e-12)
+
+
+def test_binary_levels_equal_block_sparse_attention():
+    """H = 1 (or equal thresholds): PSA is dense attention under a binary block mask."""
+    p, Q, K, V = _setup(40, N=80, d=8, bq=16, bk=16, H=1)
+    M = (np.random.default_rng(2).random((1, p.Hq, p.nq, p.nk)) < 0.5).astype(np.uint8)
+    M[..., 0] = 1
+    O, _ = orc.psa_attention(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, p)
+    np.testing.assert_allclose(O, _masked_dense(Q, K, V, M, p), rtol=1e-11, atol=1e-12)
+
+
+def test_pooled_key_weight_is_a_lower_bound():
+    """Jensen: c * exp(q.kbar) <= sum_t exp(q.k_t) for every pooled key."""
+    rng = np.random.default_rng(4)
+    k, q = rng.standard_normal((8, 6)), rng.standard_normal(6)
+    assert 8 * math.exp(q @ k.mean(0)) <= np.exp(k @ q).sum() + 1e-12
+
+
+# ---------------------------------------------------------------- Eq. 4: importance
+@pytest.mark.parametrize("est", ["max", "mean"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_importance_full_sampling_equals_block_pool_of_attention_matrix(est, causal):
+    N, bq, bk, d = 48, 8, 16, 4
+    p = Params(1, 2, 1, N, d, bq, bk, levels=2, causal=causal, sq=bq, sk=bk, rep_mode="strided", est_pool=est)
+    Q, K = _rand(50, 1, 2, N, d), _rand(51, 1, 1, N, d)
+    S = orc.importance(Q, K, p)
+    for h in range(2):
+        s = (Q[0, h] @ K[0, 0].T) * p.sm_scale
+        if causal:
+            s = np.where(np.arange(N)[None] > np.arange(N)[:, None], -np.inf, s)
+        P = np.exp(s - s.max(1, keepdims=True))
+        P /= P.sum(1, keepdims=True)
+        tiles = P.reshape(N // bq, bq, N // bk, bk)
+        ref = tiles.max(axis=(1, 3)) if est == "max" else tiles.mean(axis=(1, 3))
+        np.testing.assert_allclose(S[0, h], ref, rtol=2e-7, atol=1e-12)
+        if est == "mean":
+            np.testing.assert_allclose(S[0, h].sum(1) * bk, 1.0, rtol=1e-6)
+
+
+def test_importance_pooled_keys_are_pyramid_top_level():
+    p = Params(1, 1, 1, 128, 8, bq=32, bk=32, levels=3, dtype="bf16")
+    K = orc.round_store(_rand(60, 1, 1, 128, 8), "bf16")
+    R, pos = orc.representatives(K[0, 0], 128, 32, p.rep_k, "pooled", "bf16")
+    np.testing.assert_array_equal(R, orc.build_pyramid(K, p)[3][0, 0])
+    np.testing.assert_array_equal(pos, np.arange(32) * 4 + 3)
+
+
+def test_strided_representatives_pick_block_centres():
+    X = np.arange(40, dtype=np.float64)[:, None]
+    R, pos = orc.representatives(X, 40, 16, 4, "strided", "f32")
+    np.testing.assert_array_equal(pos, [2, 6, 10, 14, 18, 22, 26, 30, 34, 38, 39, 39])
+    np.testing.assert_array_equal(R[:, 0], pos)
+
+
+# ---------------------------------------------------------------- Alg. 2: threshold assignment
+def _golden_thresholds():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "thresholds.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, *v = line.split()
+            out[name] = tuple(float(x) for x in v)
+    return out
+
+
+def _alloc(S_row, p):
+    return orc.allocate_levels(np.asarray(S_row, dtype=np.float32)[None, None, None, :], p)[0, 0, 0]
+
+
+def test_threshold_uniform_row_hand_computed():
+    T = _golden_thresholds()["multilevel"]                            # .70 .80 .90 .90
+    p = Params(1, 1, 1, 16 * 4, 4, bq=64, bk=4, levels=4, alloc_mode="threshold", tau=T)
+    M = _alloc(np.full(16, 0.25), p)
+    # cumulative shares k/16: <= .70 for k <= 11, <= .80 for k = 12, <= .90 for k = 13, 14
+    np.testing.assert_array_equal(M, [1] * 11 + [2] + [3, 3] + [0, 0])
+    assert 4 not in M                                                   # tau_3 = tau_4: level 4 unreachable
+
+
+def test_threshold_binary_special_case():
+    T = _golden_thresholds()["binary"]
+    p = Params(1, 1, 1, 64, 4, bq=64, bk=4, levels=4, alloc_mode="threshold", tau=T)
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        M = _alloc(rng.random(16) ** 4, p)
+        assert set(np.unique(M)) <= {0, 1}
+
+
+def test_threshold_descending_shares_hand_computed():
+    # shares .4 .3 .2 .1 (given out of order); cumulative .4 .7 .9 1.0 up to rounding
+    p = Params(1, 1, 1, 16, 4, bq=16, bk=4, levels=3, alloc_mode="threshold", tau=(0.45, 0.75, 0.95))
+    np.testing.assert_array_equal(_alloc([2.0, 4.0, 1.0, 3.0], p), [3, 1, 0, 2])
+
+
+def test_threshold_one_hot_row_keeps_top_block():
+    p = Params(1, 1, 1, 32, 4, bq=32, bk=4, levels=2, alloc_mode="threshold", tau=(0.5, 0.9))
+    row = np.zeros(8)
+    row[5] = 1.0
+    np.testing.assert_array_equal(_alloc(row, p), [0, 0, 0, 0, 0, 1, 0, 0])
+    # all-zero row is treated as uniform
+    np.testing.assert_array_equal(_alloc(np.zeros(8), p), [1, 1, 1, 1, 2, 2, 2, 0])
+
+
+def test_threshold_ties_keep_lower_index_first():
+    p = Params(1, 1, 1, 16, 4, bq=16, bk=4, levels=1, alloc_mode="threshold", tau=(0.5,))
+    np.testing.assert_array_equal(_alloc([1.0, 1.0, 1.0, 1.0], p), [1, 1, 0, 0])
+
+
+def _alg2_loops(S_row, tau):
+    """Alg. 2 transcribed with python scalars (independent of numpy's sort/cumsum)."""
+    n = len(S_row)
+    tot = sum(float(x) for x in S_row)
+    E = [float(x) / tot for x in S_row]
+    order = sorted(range(n), key=lambda j: (-E[j], j))
+    M, acc = [0] * n, 0.0
+    for rank, j in enumerate(order):
+        acc += E[j]
+        lvl = 0
+        for t, th in enumerate(tau):
+            if acc <= th:
+                lvl = t + 1
+                break
+        M[j] = 1 if (rank == 0 and lvl == 0) else lvl
+    return M
+
+
+def test_threshold_random_rows_match_loop_transcription():
+    T = _golden_thresholds()["sim_preset"]
+    tau32 = [float(np.float32(t)) for t in T]
+    p = Params(1, 1, 1, 4 * 37, 4, bq=4 * 37, bk=4, levels=4, alloc_mode="threshold", tau=T)
+    rng = np.random.default_rng(1)
+    for _ in range(25):
+        row = (rng.random(37) ** 6).astype(np.float32)
+        np.testing.assert_array_equal(_alloc(row, p), _alg2_loops(row, tau32))
+
+
+# ---------------------------------------------------------------- quota rules, Eq. 9, Table 9
+def _presets():
+    rows = []
+    for line in open(os.path.join(GOLDEN, "table9_presets.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, l1, l2, l3, drop, cov = line.split()
+            rows.append((name, int(l1), int(l2), int(l3), int(drop), float(cov)))
+    return rows
+
+
+@pytest.mark.parametrize("preset", _presets(), ids=lambda r: r[0])
+def test_table9_presets_cost_quarter_of_dense(preset):
+    name, l1, l2, l3, drop, cov = preset
+    nk = 200
+    cuts = (l1 / 100, (l1 + l2) / 100, (l1 + l2 + l3) / 100)
+    p = Params(1, 1, 1, 8 * nk, 4, bq=8 * nk, bk=8, levels=3, alloc_mode="quantile", tau=cuts)
+    S = np.random.default_rng(0).random((1, 1, 1, nk)).astype(np.float32)
+    M = orc.allocate_levels(S, p)
+    counts = [int((M == h).sum()) for h in range(4)]
+    assert counts == [2 * drop, 2 * l1, 2 * l2, 2 * l3]
+    assert abs(orc.compute_ratio(M, p)[0, 0] - 0.25) < 1e-12          # Eq. 9 on the printed quotas
+    assert abs(orc.kv_coverage(M, p)[0, 0] - cov) < 1e-12
+    # finer levels go to the more important blocks
+    s = S[0, 0, 0]
+    for h in (1, 2):
+        if counts[h] and counts[h + 1]:
+            assert s[M[0, 0, 0] == h].min() >= s[M[0, 0, 0] == h + 1].max()
+
+
+def test_budget_rule_reproduces_default_preset_and_dense():
+    np.testing.assert_allclose(orc.budget_cut_points(0.25, 3), (0.15, 0.25, 0.45), atol=1e-7)
+    assert orc.budget_cut_points(1.0, 4) == (1.0, 1.0, 1.0, 1.0)
+    p = Params(1, 1, 1, 64, 4, bq=64, bk=4, levels=4, alloc_mode="budget", budget=1.0)
+    assert np.all(_alloc(np.random.default_rng(0).random(16), p) == 1)
+    # deeper pyramids fall back to fewer levels when the quotas would exceed all blocks
+    c = orc.budget_cut_points(0.5, 5)
+    assert c[-1] <= 1.0 and c[2] == c[3] == c[4]
+
+
+@pytest.mark.parametrize("beta", [0.05, 0.1, 0.2, 0.3, 0.5])
+@pytest.mark.parametrize("H", [1, 3, 4, 5])
+def test_budget_rule_meets_the_budget(beta, H):
+    nk = 512
+    p = Params(1, 1, 1, 8 * nk, 4, bq=8 * nk, bk=8 << (H - 1), levels=H, alloc_mode="budget", budget=beta)
+    p = Params(1, 1, 1, p.bk * nk, 4, bq=p.bk * nk, bk=p.bk, levels=H, alloc_mode="budget", budget=beta)
+    S = np.random.default_rng(1).random((1, 1, 1, nk)).astype(np.float32)
+    rho = orc.compute_ratio(orc.allocate_levels(S, p), p)[0, 0]
+    assert beta - 2.0 / nk <= rho <= beta + 1.0 / nk
+
+
+def test_causal_allocation_classes():
+    p = Params(1, 1, 1, 512, 4, bq=128, bk=64, levels=3, causal=True, alloc_mode="budget", budget=0.5)
+    vis = orc.block_visibility(p)
+    for i in range(4):
+        np.testing.assert_array_equal(vis[i], [1] * (2 * i) + [2, 2] + [0] * (8 - 2 * i - 2))
+    S = np.random.default_rng(2).random((1, 1, 4, 8)).astype(np.float32)
+    M = orc.allocate_levels(S, p)[0, 0]
+    assert np.all(M[vis == 0] == 0) and np.all(M[vis == 2] == 1)
+
+
+def test_level_cap_only_lowers_kept_blocks():
+    p = Params(1, 1, 1, 64, 4, bq=64, bk=4, levels=4, alloc_mode="quantile", tau=(0.25, 0.5, 0.75, 0.9))
+    S = np.random.default_rng(3).random((1, 1, 1, 16)).astype(np.float32)
+    M = orc.allocate_levels(S, p)
+    cap = np.full((1, 1, 16), 2, dtype=np.uint8)
+    Mc = orc.allocate_levels(S, p, level_cap=cap)
+    np.testing.assert_array_equal(Mc, np.where(M > 0, np.minimum(M, 2), 0))
+
+
+# ---------------------------------------------------------------- direction of the approximation
+def test_error_shrinks_with_budget_and_pyramid_beats_binary():
+    import synth_inputs as si
+    w = si.small_variant(si.CONFIGS["tiny"], 1024)
+    Q, K, V = (x.astype(np.float64) for x in si.generate_qkv(w))
+    base = dict(B=w.B, Hq=w.Hq, Hkv=w.Hkv, N=w.N, d=w.d, bq=64, bk=64, dtype="f32")
+    Od, _ = orc.dense_attention(Q, K, V, Params(levels=1, **base))
+
+    def err(H, beta):
+        p = Params(levels=H, alloc_mode="budget", budget=beta, **base)
+        M = orc.allocate_levels(orc.importance(Q, K, p), p)
+        O, _ = orc.psa_attention(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, p)
+        return np.linalg.norm(O - Od) / np.linalg.norm(Od), orc.compute_ratio(M, p).mean()
+
+    e25, r25 = err(4, 0.25)
+    e50, _ = err(4, 0.5)
+    e100, r100 = err(4, 1.0)
+    b25, rb = err(1, 0.25)
+    assert e100 < 1e-12 and r100 == 1.0
+    assert e50 < e25
+    assert r25 <= rb + 1e-12 and e25 < b25                              # no more FLOPs, smaller error
