@@ -1,0 +1,145 @@
+/*
+ * libpsa -- Pyramid Sparse Attention (PSA) forward pass for AMD MI355X (gfx950).  C ABI.
+ *
+ * The four calls are the stages of the method in "PSA: Pyramid Sparse Attention":
+ *   psa_build_pyramid    Sec. 3.2, Eq. 2-3   mean-pooled K/V pyramid
+ *   psa_allocate_levels  Sec. 3.3, Eq. 4, Alg. 2, Eq. 5-7 (+ the quantile rule of Sec. 4.4)
+ *   psa_attention_fwd    Sec. 3.4, Alg. 1, Eq. 8   online-softmax attention over mixed-level KV blocks
+ *   psa_dense_ref        Sec. 3.1, Eq. 1     plain softmax attention (reference / comparison)
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer owned by the caller unless it says "host".  The library
+ *     allocates nothing, keeps no state between calls and never synchronises: work is enqueued on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and the call returns.
+ *   - Tensors are contiguous, row-major:  Q, O: [B, Hq, N, d];  K, V: [B, Hkv, N, d].
+ *     Query head hq reads key/value head hq / (Hq / Hkv).  Element type is psa_params.dtype
+ *     (bfloat16 or float32) for Q, K, V, the pyramids and O.
+ *   - Blocks (Sec. 3.1): nq = ceil(N / bq) query blocks, nk = ceil(N / bk) key blocks; the last block
+ *     of either kind may be short (the paper assumes divisibility; see psa_build_pyramid).
+ *   - Levels follow Eq. 5:  M = 0 skip,  M = h in 1..H use level h (pooled by 2^(h-1)).
+ *   - Return value: PSA_OK, or an error code; on error nothing has been enqueued.
+ *     No call prints, throws or aborts.
+ */
+#ifndef PSA_H
+#define PSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { PSA_OK = 0, PSA_EINVAL = 1, PSA_EUNSUPPORTED = 2, PSA_ELAUNCH = 3 };
+
+enum { PSA_BF16 = 0, PSA_F32 = 1 };
+enum { PSA_REP_STRIDED = 0, PSA_REP_POOLED = 1 };
+enum { PSA_EST_MAX = 0, PSA_EST_MEAN = 1 };
+enum { PSA_ALLOC_THRESHOLD = 0, PSA_ALLOC_QUANTILE = 1, PSA_ALLOC_BUDGET = 2 };
+
+#define PSA_MAX_LEVELS 8
+#define PSA_MAX_NK 4096 /* key blocks per row the allocation kernel can sort */
+
+typedef struct psa_params {
+  int32_t B, Hq, Hkv, N, d; /* shapes; Hq % Hkv == 0; d in {64, 128}                                  */
+  int32_t bq, bk, levels;   /* block sizes (Sec. 3.1) and pyramid depth H in 1..8; bk a power of two,  */
+                            /* bk >> (H-1) >= 1; bq a multiple of 8                                     */
+  int32_t dtype;            /* PSA_BF16 | PSA_F32                                                       */
+  int32_t causal;           /* 0 | 1: token-level causal mask (key index <= query index)                */
+  float scale;              /* softmax scale; 0 selects 1/sqrt(d) (Alg. 1 input)                        */
+  int32_t sq, sk;           /* representatives per query / key block (the sampled tokens of Eq. 4);     */
+                            /* 0 selects sq = min(8, bq), sk = bk >> (H-1).  POOLED needs sq|bq, sk|bk  */
+  int32_t rep_mode;         /* PSA_REP_STRIDED: token  start + floor((t+1/2) b/s);  PSA_REP_POOLED:     */
+                            /* mean of the t-th of s contiguous groups (rounded to dtype)               */
+  int32_t est_pool;         /* PSA_EST_MAX (Eq. 4) | PSA_EST_MEAN (App. B.2 variant)                    */
+  int32_t alloc_mode;       /* PSA_ALLOC_THRESHOLD (Alg. 2) | PSA_ALLOC_QUANTILE | PSA_ALLOC_BUDGET     */
+  float tau[PSA_MAX_LEVELS];/* THRESHOLD: tau_1 <= ... <= tau_H in [0,1] (Eq. 6).  QUANTILE: cumulative */
+                            /* block fractions a_1 <= ... <= a_H in [0,1] (Sec. 4.4).  BUDGET: unused   */
+  float budget;             /* BUDGET: target compute ratio rho-bar of Eq. 9, in (0, 1]                 */
+} psa_params;
+
+/*
+ * Sizes the caller must provide (host call, no GPU work).
+ *   pyr_bytes      bytes of ONE pyramid buffer (Kpyr or Vpyr): levels 2..H, level-major; level h is
+ *                  [B, Hkv, nk * (bk >> (h-1)), d] and starts where level h-1 ends (level 1 is K / V
+ *                  itself and is not copied).  0 when H = 1.
+ *   scratch_bytes  bytes of workspace that psa_allocate_levels and psa_attention_fwd may use
+ *                  (representative tokens, scores, per-row block lists).  Contents need not survive
+ *                  between calls.  Must be 256-byte aligned.
+ * Either output pointer may be NULL.  Errors: PSA_EINVAL / PSA_EUNSUPPORTED for bad parameters.
+ */
+int psa_query_sizes(const psa_params* p, size_t* pyr_bytes, size_t* scratch_bytes);
+
+/*
+ * Pyramid KV blocks, Eq. 2-3:  K^1 = K,  K^{h+1} = MeanPool(K^h, 2, 2), same for V.
+ * Writes levels 2..H of both tensors into Kpyr / Vpyr (layout above) in one pass over K and V.
+ * Level h is the mean of the 2^(h-1) level-1 tokens it covers, accumulated in fp32 and rounded once
+ * to dtype.  Ragged tail: a pooled token covering c < 2^(h-1) valid tokens is the mean of those c;
+ * pooled tokens past the end (block padding) are written as zeros.
+ * H = 1: nothing to do, returns PSA_OK (Kpyr / Vpyr may be NULL).
+ */
+int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* Kpyr, void* Vpyr,
+                      void* stream);
+
+/*
+ * Multi-level mask generator, Sec. 3.3.
+ *   Importance (Eq. 4):  S_ij = max (or mean) over the s_q x s_k representative-token pairs of
+ *   block pair (i, j) of  Softmax_row(Q~ K~^T * scale), the softmax running over the representative
+ *   keys of all key blocks.  Skipped when scores_in is given.
+ *   Assignment:  THRESHOLD = Alg. 2 (row-normalise, stable descending sort, inclusive cumulative sum
+ *   in fp64, M = min{t : S^ <= tau_t}, else 0);  QUANTILE = rank r gets min{h : r < floor(a_h n + 1e-3)};
+ *   BUDGET = QUANTILE with a_h derived from `budget` (level 1 gets 60 % of the budget FLOPs, levels
+ *   2..H' share 40 % equally; H' the deepest level count whose quotas fit).  In every mode the
+ *   top-ranked block of a row is kept (level 1) if the rule would skip it; causal: invisible blocks
+ *   are 0 and do not count, blocks straddling the diagonal are level 1.
+ * Arguments
+ *   Q, K        inputs (K unused when rep_mode = POOLED and sk = bk >> (H-1): Kpyr's last level is read)
+ *   Kpyr        K pyramid from psa_build_pyramid (may be NULL if H = 1 or not needed as above)
+ *   scores_in   nullable, float [B, Hq, nq, nk]: use these scores instead of estimating them
+ *   scores_out  nullable, float [B, Hq, nq, nk]: receives S
+ *   level_cap   nullable, uint8 [B, Hkv, nk], values 1..H: per-block maximum level (App. B.1);
+ *               kept blocks get min(M, cap), skipped blocks stay skipped
+ *   M           out, uint8 [B, Hq, nq, nk]
+ *   rho_out     nullable, float [B, Hq]: achieved compute ratio, Eq. 9, over the visible block pairs
+ *   scratch     workspace of psa_query_sizes' scratch_bytes
+ * Errors: PSA_EINVAL (null required pointer, tau not monotone / outside [0,1], budget outside (0,1]),
+ *         PSA_EUNSUPPORTED (nk > PSA_MAX_NK, d not in {64,128}), PSA_ELAUNCH.
+ */
+int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const void* Kpyr,
+                        const float* scores_in, float* scores_out, const uint8_t* level_cap,
+                        uint8_t* M, float* rho_out, void* scratch, void* stream);
+
+/*
+ * Adaptive pyramid attention, Alg. 1 / Eq. 8.  For every query block i and every key block j with
+ * h = M_ij > 0:  s = Q_i K_j^{h T} * scale + (h-1) ln 2, online softmax, o += P V_j^h;  O_i = o / l.
+ * Key blocks of a row may be visited in any order (the result does not depend on it beyond rounding).
+ * A pooled key covering c valid tokens of a ragged last block is biased by ln c; padding is masked.
+ * Causal: a (pooled) key is visible to a query row iff every token it covers is <= the row.
+ *   K, V        level 1;  Kpyr, Vpyr  levels 2..H (may be NULL if H = 1)
+ *   M           uint8 [B, Hq, nq, nk] (values > H are an error the kernel does not detect: undefined)
+ *   O           out [B, Hq, N, d], dtype
+ *   lse         nullable out, float [B, Hq, N]: natural-log softmax denominator incl. the row max
+ *   scratch     workspace of psa_query_sizes' scratch_bytes (per-row level-sorted block lists)
+ * bfloat16: QK^T and PV run on MFMA with fp32 accumulation, P is rounded to bfloat16 before PV.
+ * float32: all arithmetic in fp32 with an accurate exp.
+ * A row whose kept blocks contain no visible key produces NaN.
+ */
+int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const void* V,
+                      const void* Kpyr, const void* Vpyr, const uint8_t* M, void* O, float* lse,
+                      void* scratch, void* stream);
+
+/*
+ * Dense softmax attention, Eq. 1 (optionally causal / grouped-query): O = Softmax(Q K^T * scale) V.
+ * A simple fp32-accumulate kernel meant as a reference, not as a fast path.
+ *   O  out [B, Hq, N, d], dtype;  lse nullable out, float [B, Hq, N].
+ */
+int psa_dense_ref(const psa_params* p, const void* Q, const void* K, const void* V, void* O,
+                  float* lse, void* stream);
+
+/* Static description of a status code (host pointer, never NULL). */
+const char* psa_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSA_H */

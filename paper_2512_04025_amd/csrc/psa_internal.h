@@ -1,0 +1,49 @@
+// Host-side plan (validated, derived parameters) and the kernel launchers behind the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/psa.h"
+
+namespace psa {
+
+struct Plan {
+  int B, Hq, Hkv, N, d, bq, bk, H, dtype, causal;
+  float scale;
+  int sq, sk, rep_mode, est_pool, alloc_mode;
+  int nq, nk, group, esize;
+  // element offset of level h (2..H) inside one pyramid buffer; level h is [B, Hkv, nk*(bk>>(h-1)), d]
+  int64_t lvl_off[PSA_MAX_LEVELS + 2];
+  int64_t pyr_elems;
+  float tau[PSA_MAX_LEVELS];
+  double cuts[PSA_MAX_LEVELS];  // cumulative block quotas (QUANTILE / BUDGET)
+  bool krep_is_pyramid;         // representative keys are exactly pyramid level H
+  bool use_mfma;                // bf16 tensor-core attention kernel applies
+  // scratch layout (byte offsets, 256-aligned)
+  size_t off_qrep, off_krep, off_scores, off_rowcnt, off_idx, off_cnt, scratch_bytes;
+};
+
+int make_plan(const psa_params* p, Plan* out);
+
+// rows of the per-row counters written by the allocation kernel: [n_visible, c_1 .. c_H]
+constexpr int ROWCNT_STRIDE = PSA_MAX_LEVELS + 1;
+// per-row level counts consumed by the attention kernels: c_1 .. c_H
+constexpr int CNT_STRIDE = PSA_MAX_LEVELS;
+
+hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s);
+hipError_t launch_representatives(const Plan& pl, const void* X, void* R, bool is_query, hipStream_t s);
+hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, float* S, hipStream_t s);
+hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, uint8_t* M, uint32_t* rowcnt,
+                           hipStream_t s);
+hipError_t launch_rho(const Plan& pl, const uint32_t* rowcnt, float* rho, hipStream_t s);
+hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int32_t* cnt, hipStream_t s);
+// idx == nullptr selects dense attention (every key block at level 1)
+hipError_t launch_attn_rows(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
+                            const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
+                            hipStream_t s);
+hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
+                            const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
+                            hipStream_t s);
+
+}  // namespace psa

@@ -1,0 +1,80 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header declares,
+reports sizes consistent with the documented layouts and rejects bad parameters before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_04025_amd as psa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(psa.library_path()):
+        from paper_2512_04025_amd.build import build_library
+        build_library(verbose=False)
+    return psa.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    header = open(os.path.join(ROOT, "include", "psa.h")).read()
+    names = set(re.findall(r"\b(psa_[a-z_]+)\s*\(", header))
+    assert {"psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_dense_ref",
+            "psa_status_str"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches_header():
+    # 16 int32/float scalars + 8 floats + 1 float, no padding
+    assert ctypes.sizeof(psa.PsaParams) == 4 * (16 + 8 + 1)
+
+
+def test_query_sizes_follow_the_documented_layout(lib):
+    p = psa.make_params(1, 12, 12, 32760, 128, 128, 64, 4)
+    pyr, scratch = psa.psa_query_sizes(p)
+    nk = -(-32760 // 64)
+    assert pyr == 12 * nk * (32 + 16 + 8) * 128 * 2
+    assert scratch % 256 == 0 and scratch > 0
+    p1 = psa.make_params(1, 2, 2, 1024, 64, 64, 64, 1, dtype=psa.PSA_F32)
+    assert psa.psa_query_sizes(p1)[0] == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(Hq=3, Hkv=2), 1), (dict(levels=0), 1), (dict(levels=9), 1), (dict(bk=48), 1), (dict(bq=12), 1),
+    (dict(bk=4, levels=4), 1), (dict(dtype=7), 1), (dict(scale=-1.0), 1), (dict(N=0), 1),
+    (dict(sq=256), 1), (dict(rep_mode=5), 1), (dict(d=96), 2), (dict(sk=3, rep_mode=0), 2),
+])
+def test_bad_parameters_are_rejected(lib, kw, status):
+    base = dict(B=1, Hq=2, Hkv=2, N=1024, d=64, bq=64, bk=64, levels=4)
+    base.update(kw)
+    p = psa.make_params(**base)
+    with pytest.raises(psa.PsaError) as e:
+        psa.psa_query_sizes(p)
+    assert e.value.status == status
+
+
+def test_null_pointers_and_bad_rules_fail_before_any_launch(lib):
+    p = psa.make_params(1, 2, 2, 1024, 64, 64, 64, 4, alloc_mode=psa.PSA_ALLOC_THRESHOLD, tau=(0.9, 0.5, 0.9, 0.9))
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    pp = ctypes.byref(p)
+    assert lib.psa_build_pyramid(pp, None, None, None, None, None) == 1
+    assert lib.psa_allocate_levels(pp, None, None, None, one, None, None, one, None, one, None) == 1   # tau not monotone
+    assert lib.psa_attention_fwd(pp, None, None, None, None, None, None, None, None, None, None) == 1
+    assert lib.psa_dense_ref(pp, None, None, None, None, None, None) == 1
+    pb = psa.make_params(1, 2, 2, 1024, 64, 64, 64, 4, budget=0.0)
+    assert lib.psa_allocate_levels(ctypes.byref(pb), None, None, None, one, None, None, one, None, one, None) == 1
+    pb.budget = 1.5
+    assert lib.psa_allocate_levels(ctypes.byref(pb), None, None, None, one, None, None, one, None, one, None) == 1
+    assert psa.psa_status_str(0) == "ok" and "unknown" in psa.psa_status_str(99)
+
+
+def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
+    from paper_2512_04025_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libpsa.so"))
+    with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+        binding.load_library()
