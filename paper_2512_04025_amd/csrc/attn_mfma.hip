@@ -37,9 +37,19 @@ constexpr float LAZY_RESCALE = 8.0f;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 
-struct TileCursor {        // walks the tiles of one query block: level-major, then tile in level
-  int h, tl, ntl, lvl_start, nblk;
+// Scalar (wave-uniform) description of the level the loader is walking.
+struct LevelState {
+  int h;            // level, 1..H ; H+1 = past the end
+  int lg_th;        // log2(pooled tokens per block)
+  int nblk;         // kept blocks of this level
+  int ntl;          // tiles of this level
+  int lvl_start;    // position of the level's first block in the row's list
+  int lim;          // pooled rows >= lim are partly invalid (ragged tail) or not visible to every row
+  int rowmax;       // clamp for the source row (level 1 is not padded to whole blocks)
+  const char* kbase;
+  const char* vbase;
 };
 
 template <int D, int NW>
@@ -47,26 +57,33 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp, const uint16_t* __restrict__ idx,
     const int32_t* __restrict__ cnt, bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
+  constexpr int NT = NW * 64;
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;              // tile rows covered by one wave-wide 16 B/lane load
   constexpr int NINST = BN / RPI;            // such loads per tensor per tile
   constexpr int RI = NINST / NW;             // per wavefront
   constexpr int RP256 = 16 / CPR;            // rows per 256 bytes of LDS
+  constexpr int ROWB = D * 2;                // bytes per row
+  constexpr int TILEB = BN * ROWB;           // bytes per tile (a power of two)
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-  typedef bf16_t tile_t[BN * D];
-  tile_t* Kbuf = reinterpret_cast<tile_t*>(smem_raw);                    // [2][BN * D]
-  tile_t* Vbuf = Kbuf + 2;                                               // [2][BN * D]
-  typedef float colf_t[BN];
-  typedef int coli_t[BN];
-  colf_t* colbias = reinterpret_cast<colf_t*>(Vbuf + 2);                 // [2][BN] log2(valid tokens) or -inf
-  coli_t* collast = reinterpret_cast<coli_t*>(colbias + 2);              // [2][BN] last token under the key
-  int* special = reinterpret_cast<int*>(collast + 2);                    // [2] tile number + 1 if irregular
+  // LDS map: K[2] | V[2] | rowinfo[2][64] | tilebias[2] | special[2] | block list
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_ROWINFO = 4 * TILEB;
+  constexpr int OFF_TBIAS = OFF_ROWINFO + 2 * BN * 4, OFF_SPECIAL = OFF_TBIAS + 8, OFF_LIST = OFF_SPECIAL + 8;
+  int* rowinfo = reinterpret_cast<int*>(smem + OFF_ROWINFO);        // [2][BN] source row, -1 = no key
+  float* tilebias = reinterpret_cast<float*>(smem + OFF_TBIAS);     // [2] level - 1
+  int* special = reinterpret_cast<int*>(smem + OFF_SPECIAL);        // [2] tile number + 1 if irregular
+  uint16_t* list = reinterpret_cast<uint16_t*>(smem + OFF_LIST);    // kept block ids, level-major
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
-  const int item = blockIdx.x;
-  if (item >= a.items) return;
+  // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
+  // contiguous run of (head, query block) items, so the workgroups that share an L2 at any moment are
+  // neighbouring query blocks of one head: they keep similar key blocks and walk them in the same order.
+  const int per_xcd = (a.items + 7) >> 3;
+  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per_xcd || item >= a.items) return;
   const int slice = item % a.slices;
   int i = (item / a.slices) % a.nq;
   if (a.causal) i = a.nq - 1 - i;            // longest rows first
@@ -82,94 +99,88 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 
   const int64_t srow = qhead * a.nq + i;
   const uint16_t* my_idx = idx + srow * a.nk;
-  int lcnt[PSA_MAX_LEVELS];
-#pragma unroll
-  for (int h = 0; h < PSA_MAX_LEVELS; ++h) lcnt[h] = h < a.H ? cnt[srow * CNT_STRIDE + h] : 0;
+  const int32_t* my_cnt = cnt + srow * CNT_STRIDE;
 
-  auto tiles_in_level = [&](int h, int nblk) {
+  // ---- totals and the block list into LDS
+  int total_blocks = 0, total_tiles = 0;
+  for (int h = 1; h <= a.H; ++h) {
+    const int nb = my_cnt[h - 1];
     const int lg_th = a.lg_bk - (h - 1);
-    return lg_th >= 6 ? nblk << (lg_th - 6) : (nblk + (1 << (6 - lg_th)) - 1) >> (6 - lg_th);
-  };
-  auto advance = [&](TileCursor& c) {       // move to the next tile; h > H means done
-    ++c.tl;
-    while (c.h <= a.H && c.tl >= c.ntl) {
-      c.lvl_start += c.nblk;
-      ++c.h;
-      c.tl = 0;
-      c.nblk = c.h <= a.H ? lcnt[c.h - 1] : 0;
-      c.ntl = c.h <= a.H ? tiles_in_level(c.h, c.nblk) : 0;
+    total_blocks += nb;
+    total_tiles += ((nb << lg_th) + BN - 1) >> 6;
+  }
+  for (int x = tid; x < total_blocks; x += NT) list[x] = my_idx[x];
+
+  LevelState ls;
+  auto enter_level = [&](int h, int lvl_start) {   // scalar work, once per level
+    ls.h = h;
+    ls.lvl_start = lvl_start;
+    if (h > a.H) { ls.nblk = 0; ls.ntl = 0; return; }
+    ls.lg_th = a.lg_bk - (h - 1);
+    ls.nblk = my_cnt[h - 1];
+    ls.ntl = ((ls.nblk << ls.lg_th) + BN - 1) >> 6;
+    int lim = a.N >> (h - 1);                                  // rows below cover 2^(h-1) valid tokens
+    if (a.causal) {
+      const int vis = (row0 + 1) >> (h - 1);                   // rows below end at or before row0
+      lim = vis < lim ? vis : lim;
+    }
+    ls.lim = lim;
+    ls.rowmax = h == 1 ? a.N - 1 : 0x7fffffff;
+    const int64_t rows_h = (int64_t)a.nk << ls.lg_th;
+    if (h == 1) {
+      ls.kbase = reinterpret_cast<const char*>(K + khead * (int64_t)a.N * D);
+      ls.vbase = reinterpret_cast<const char*>(V + khead * (int64_t)a.N * D);
+    } else {
+      ls.kbase = reinterpret_cast<const char*>(Kp + a.lvl_off[h] + khead * rows_h * D);
+      ls.vbase = reinterpret_cast<const char*>(Vp + a.lvl_off[h] + khead * rows_h * D);
     }
   };
-  TileCursor cur;
-  cur.h = 1; cur.tl = -1; cur.lvl_start = 0; cur.nblk = lcnt[0]; cur.ntl = tiles_in_level(1, cur.nblk);
-  advance(cur);
-  TileCursor nxt = cur;                      // tile whose rows are fetched next
-  TileCursor pre = cur;                      // tile whose block ids are fetched next
+  int ld_tl = 0;                              // loader's tile index inside its level
+  enter_level(1, 0);
+  while (ls.h <= a.H && ls.ntl == 0) enter_level(ls.h + 1, ls.lvl_start + ls.nblk);
 
-  // ---- per-lane constants of the loader: tile row and chunk position of each of its RI loads
+  // ---- per-lane constants of the loader
   const int lrow = lane / CPR;               // row within one load instruction
   const int lpos = lane % CPR;               // 16-byte slot within the LDS row
-  int jreg[RI];                              // block id (clamped) of each row for the tile under `pre`
-
-  auto fetch_ids = [&](const TileCursor& c) {
-    const int lg_th = a.lg_bk - (c.h - 1);
+  int r_k[RI];
+  uint32_t kswz[RI], vswz[RI];
 #pragma unroll
-    for (int k = 0; k < RI; ++k) {
-      const int r = (k * NW + wave) * RPI + lrow;
-      int e = lg_th >= 6 ? c.tl >> (lg_th - 6) : (c.tl << (6 - lg_th)) + (r >> lg_th);
-      e = e < c.nblk ? e : c.nblk - 1;
-      jreg[k] = (int)my_idx[c.lvl_start + e];
-    }
-  };
+  for (int k = 0; k < RI; ++k) {
+    const int r = (k * NW + wave) * RPI + lrow;
+    r_k[k] = r;
+    kswz[k] = (uint32_t)((lpos ^ ((r / RP256) % CPR)) << 4);              // spreads 16 rows over all banks
+    vswz[k] = (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);  // spreads 4 rows x 64 B
+  }
 
-  // issue the direct-to-LDS loads of the tile under c into buffer `slot`; jreg holds its block ids
-  auto fetch_rows = [&](const TileCursor& c, int slot, int tileno) {
-    const int h = c.h;
-    const int lg_th = a.lg_bk - (h - 1);
-    const int th = 1 << lg_th, span = 1 << (h - 1);
-    const bf16_t* kbase;
-    const bf16_t* vbase;
-    if (h == 1) {
-      kbase = K + khead * (int64_t)a.N * D;
-      vbase = V + khead * (int64_t)a.N * D;
-    } else {
-      kbase = Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
-      vbase = Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
-    }
+  // issue the direct-to-LDS loads of the loader's current tile into buffer `slot`, then step it
+  auto issue_tile = [&](int slot, int tileno) {
+    const int g0 = ld_tl << 6;
+    const int thm1 = (1 << ls.lg_th) - 1;
     bool irregular = false;
 #pragma unroll
     for (int k = 0; k < RI; ++k) {
+      const int g = g0 + r_k[k];                               // position in the level's token stream
+      const int e = g >> ls.lg_th;                             // list entry
+      const int ec = e < ls.nblk ? e : ls.nblk - 1;
+      const int j = (int)list[ls.lvl_start + ec];
+      const int prow = (j << ls.lg_th) | (g & thm1);           // row in the level-h array
+      irregular |= (e >= ls.nblk) | (prow >= ls.lim);
+      const int prow_c = prow < ls.rowmax ? prow : ls.rowmax;
+      const uint32_t voff = (uint32_t)prow_c * (uint32_t)ROWB;
       const int inst = k * NW + wave;
-      const int r = inst * RPI + lrow;
-      int e, within;
-      if (lg_th >= 6) {
-        e = c.tl >> (lg_th - 6);
-        within = ((c.tl & ((1 << (lg_th - 6)) - 1)) << 6) + r;
-      } else {
-        e = (c.tl << (6 - lg_th)) + (r >> lg_th);
-        within = r & (th - 1);
-      }
-      const int prow = (jreg[k] << lg_th) + within;
-      const int first_tok = prow << (h - 1);
-      int cvalid = a.N - first_tok;
-      cvalid = cvalid < 0 ? 0 : (cvalid > span ? span : cvalid);
-      if (e >= c.nblk) cvalid = 0;
-      const int last = first_tok + (cvalid > 0 ? cvalid : 1) - 1;
-      int lrow_src = prow;
-      if (h == 1 && lrow_src >= a.N) lrow_src = a.N - 1;   // level 1 is not padded: stay in bounds
-      const int fk = (r / RP256) % CPR;                     // K swizzle: spreads 16 rows over all banks
-      const int fv = ((r / RP256) % (CPR / 4)) * 4;         // V swizzle: spreads 4 rows x 64 B
-      const bf16_t* ksrc = kbase + (int64_t)lrow_src * D + ((lpos ^ fk) << 3);
-      const bf16_t* vsrc = vbase + (int64_t)lrow_src * D + ((lpos ^ fv) << 3);
-      __builtin_amdgcn_global_load_lds((gbl_void*)ksrc, (lds_void*)&Kbuf[slot][inst * RPI * D], 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gbl_void*)vsrc, (lds_void*)&Vbuf[slot][inst * RPI * D], 16, 0, 0);
-      if (lpos == 0) {
-        colbias[slot][r] = cvalid > 0 ? __log2f((float)cvalid) : -INFINITY;
-        collast[slot][r] = last;
-      }
-      irregular |= cvalid != span || (a.causal && last > row0);
+      __builtin_amdgcn_global_load_lds((gbl_void*)(ls.kbase + (voff + kswz[k])),
+                                       (lds_void*)(smem + OFF_K + slot * TILEB + inst * RPI * ROWB), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gbl_void*)(ls.vbase + (voff + vswz[k])),
+                                       (lds_void*)(smem + OFF_V + slot * TILEB + inst * RPI * ROWB), 16, 0, 0);
+      if (lpos == 0) rowinfo[slot * BN + r_k[k]] = e < ls.nblk ? prow : -1;
     }
-    if (irregular) special[slot] = tileno + 1;
+    if (__any(irregular)) special[slot] = tileno + 1;
+    if (tid == 0) tilebias[slot] = (float)(ls.h - 1);
+    ++ld_tl;
+    if (ld_tl >= ls.ntl) {
+      ld_tl = 0;
+      do { enter_level(ls.h + 1, ls.lvl_start + ls.nblk); } while (ls.h <= a.H && ls.ntl == 0);
+    }
   };
 
   if (tid == 0) { special[0] = 0; special[1] = 0; }
@@ -193,64 +204,93 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     for (int v = 0; v < 16; ++v) oacc[md][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- per-lane LDS read offsets (elements)
-  // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ fk(row); fk does not depend on mb
-  const int fk_rd = (l32 / RP256) % CPR;
-  // V^T operand through the transposing load: the 16 lanes of a group address 4 rows x 32 B
-  const int grp = lane >> 4, s16 = lane & 15;
-  const int v_e = s16 >> 2, v_q = s16 & 3, v_dsel = grp & 1;
-  const int fv_rd = ((v_e / RP256) % (CPR / 4)) * 4;        // rows ks*16 + hf*4 + e (+8): row % 4 == e
-  const int v_row = hf * 4 + v_e;
-
-  __syncthreads();                           // special[] initialised
-  if (cur.h <= a.H) {
-    fetch_ids(pre);
-    fetch_rows(nxt, 0, 0);
-    advance(nxt);
-    advance(pre);
-    if (pre.h <= a.H) fetch_ids(pre);
+  // ---- per-lane LDS read addresses (bytes, buffer 0; XOR with TILEB flips the buffer)
+  // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ swizzle(row); the swizzle does not depend on mb
+  uint32_t kaddr[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    kaddr[ks] = (uint32_t)(OFF_K + l32 * ROWB + (((2 * ks + hf) ^ ((l32 / RP256) % CPR)) << 4));
+  // V^T operand through the transposing load: the 16 lanes of a group address 4 rows x 32 B; lane
+  // (group g, s) receives channel md*32 + (g&1)*16 + s of the rows addressed by lanes s/4 + {0,4,8,12}
+  uint32_t vaddr[D / 32];
+  {
+    const int grp = lane >> 4, s16 = lane & 15;
+    const int v_e = s16 >> 2, v_q = s16 & 3, v_dsel = grp & 1;
+    const int v_row = hf * 4 + v_e;
+    const int fv_rd = ((v_row / RP256) % (CPR / 4)) * 4;
+#pragma unroll
+    for (int md = 0; md < D / 32; ++md)
+      vaddr[md] = (uint32_t)(OFF_V + v_row * ROWB + (((md * 4 + v_dsel * 2 + (v_q >> 1)) ^ fv_rd) << 4) + (v_q & 1) * 8);
   }
-  int t = 0;
-  while (cur.h <= a.H) {
-    const int h = cur.h;
+
+  __syncthreads();                           // block list and special[] are in LDS
+  if (total_tiles > 0) issue_tile(0, 0);
+  for (int t = 0; t < total_tiles; ++t) {
     const int slot = t & 1;
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's loads of tile t have landed
     __syncthreads();                          // ... and everyone else's; tile t-1 fully consumed
-    if (nxt.h <= a.H) {
-      fetch_rows(nxt, slot ^ 1, t + 1);       // overlaps with the math below
-      advance(nxt);
-      advance(pre);
-      if (pre.h <= a.H) fetch_ids(pre);
-    }
-    advance(cur);
-    const bf16_t* Ks = Kbuf[slot];
-    const bf16_t* Vs = Vbuf[slot];
+    if (t + 1 < total_tiles) issue_tile(slot ^ 1, t + 1);   // overlaps with the math below
+
+    // ---- operand fetch: every K fragment of the tile and the V^T fragments of the first half of
+    //      the channels are requested from LDS up front, so the matrix pipe never waits on a
+    //      single outstanding read
+    auto read_vt = [&](int md, int ks) {
+      const unsigned char* vp = smem + vaddr[md] + ks * 16 * ROWB;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
+      return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    constexpr int MDH = D / 64;              // channel blocks per half
+    bf16x8 kfr[2][D / 16];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks)
+        kfr[mb][ks] = *reinterpret_cast<const bf16x8*>(smem + kaddr[ks] + mb * 32 * ROWB);
+    bf16x8 vfa[MDH][4];
+#pragma unroll
+    for (int md = 0; md < MDH; ++md)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) vfa[md][ks] = read_vt(md, ks);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- S^T = K Q^T : two 32-row halves of the 64 key columns
     f32x16 sacc[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[mb][v] = 0.f;
-#pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[(mb * 32 + l32) * D + (((2 * ks + hf) ^ fk_rd) << 3)]);
-        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sacc[mb], 0, 0, 0);
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[mb][ks], qf[ks], zero, 0, 0, 0);
+        } else {
+          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[mb][ks], qf[ks], sacc[mb], 0, 0, 0);
+        }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- online softmax (log2 domain).  register v of half mb is key column
     //      mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
-    float tmax = -INFINITY;
+    const float tbias = tilebias[slot];
     const bool slow = special[slot] == t + 1;
+    float tmax = -INFINITY;
     if (slow) {
+      const int hm1 = (int)tbias;
+      const int span = 1 << hm1;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int col = mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-          float x = sacc[mb][v] * a.scale_log2 + colbias[slot][col];
-          if (a.causal && collast[slot][col] > qrow) x = -INFINITY;
+          const int pr = rowinfo[slot * BN + col];
+          const int first = pr << hm1;
+          int c = a.N - first;
+          c = c < 0 ? 0 : (c > span ? span : c);
+          if (pr < 0) c = 0;
+          float x = sacc[mb][v] * a.scale_log2 + __log2f((float)c);   // log2(0) = -inf masks the key
+          if (a.causal && first + c - 1 > qrow) x = -INFINITY;
+          if (c == 0) x = -INFINITY;
           sacc[mb][v] = x;
           tmax = fmaxf(tmax, x);
         }
@@ -259,7 +299,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[mb][v]);
-      tmax = tmax * a.scale_log2 + (float)(h - 1);
+      tmax = tmax * a.scale_log2 + tbias;
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
     if (__any(tmax - m_run > LAZY_RESCALE)) {
@@ -284,7 +324,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
           pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
         }
     } else {
-      const float shift = (float)(h - 1) - m_use;
+      const float shift = tbias - m_use;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -296,23 +336,29 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     }
 
     // ---- O^T += V^T P^T : contraction index (hf, e) of k-step ks is key column
-    //      ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers above.  The transposing load
-    //      hands lane (group g, s) the 4 values of channel md*32 + (g&1)*16 + s from the 4 rows
-    //      addressed by lanes s/4 + {0,4,8,12} of its group.
+    //      ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers above
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 vfb[MDH][4];
 #pragma unroll
-    for (int md = 0; md < D / 32; ++md) {
+    for (int md = 0; md < MDH; ++md)
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const int chunk = ((md * 4 + v_dsel * 2 + (v_q >> 1)) ^ fv_rd);
-        const bf16_t* vp = &Vs[(ks * 16 + v_row) * D + (chunk << 3) + (v_q & 1) * 4];
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * D));
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[ks], oacc[md], 0, 0, 0);
-      }
-    }
-    ++t;
+      for (int ks = 0; ks < 4; ++ks) vfb[md][ks] = read_vt(MDH + md, ks);
+#pragma unroll
+    for (int md = 0; md < MDH; ++md)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa[md][ks], pf[ks], oacc[md], 0, 0, 0);
+#pragma unroll
+    for (int md = 0; md < MDH; ++md)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        oacc[MDH + md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb[md][ks], pf[ks], oacc[MDH + md], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // flip the LDS read addresses to the other buffer
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) kaddr[ks] ^= (uint32_t)TILEB;
+#pragma unroll
+    for (int md = 0; md < D / 32; ++md) vaddr[md] ^= (uint32_t)TILEB;
   }
 
   // ---- epilogue: O = o / l ; lane (qrow, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
@@ -324,15 +370,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     for (int md = 0; md < D / 32; ++md)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const uint32_t w0 = (uint32_t)f32_to_bf16(oacc[md][4 * g] * inv) |
-                            ((uint32_t)f32_to_bf16(oacc[md][4 * g + 1] * inv) << 16);
-        const uint32_t w1 = (uint32_t)f32_to_bf16(oacc[md][4 * g + 2] * inv) |
-                            ((uint32_t)f32_to_bf16(oacc[md][4 * g + 3] * inv) << 16);
-        const u32x2 w = {w0, w1};
-        *reinterpret_cast<u32x2*>(op + md * 32 + g * 8 + hf * 4) = w;
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[md][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + md * 32 + g * 8 + hf * 4) = w;
       }
     if (lse && hf == 0) lse[qhead * a.N + qrow] = (m_run + __log2f(l_tot)) * 0.69314718055994531f;
   }
+}
+
+size_t attn_mfma_smem_bytes(int d, int nk) {
+  return 4 * (size_t)BN * d * sizeof(bf16_t) + 2 * BN * sizeof(int) + 16 + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
 template <int D, int NW>
@@ -348,12 +396,12 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.items = pl.B * pl.Hq * pl.nq * a.slices;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
-  const size_t smem = 4 * (size_t)BN * D * sizeof(bf16_t) + 4 * BN * sizeof(float) + 16;
+  const size_t smem = attn_mfma_smem_bytes(D, pl.nk);
   auto kern = attn_mfma_kernel<D, NW>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)smem);
   if (e != hipSuccess) return e;
-  kern<<<a.items, NW * 64, smem, s>>>(
+  kern<<<((a.items + 7) / 8) * 8, NW * 64, smem, s>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
       static_cast<const bf16_t*>(Kp), static_cast<const bf16_t*>(Vp), idx, cnt, static_cast<bf16_t*>(O), lse, a);
   return hipGetLastError();
