@@ -66,13 +66,13 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
   constexpr int ROWB = D * 2;                // bytes per row
   constexpr int TILEB = BN * ROWB;           // bytes per tile (a power of two)
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-  // LDS map: K[2] | V[2] | rowinfo[2][64] | tilebias[2] | special[2] | block list
+  // LDS map: K[2] | V[2] | rowinfo[4][64] | tilebias[4] | special[4] | block list
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_ROWINFO = 4 * TILEB;
-  constexpr int OFF_TBIAS = OFF_ROWINFO + 2 * BN * 4, OFF_SPECIAL = OFF_TBIAS + 8, OFF_LIST = OFF_SPECIAL + 8;
-  int* rowinfo = reinterpret_cast<int*>(smem + OFF_ROWINFO);        // [2][BN] source row, -1 = no key
-  float* tilebias = reinterpret_cast<float*>(smem + OFF_TBIAS);     // [2] level - 1
-  int* special = reinterpret_cast<int*>(smem + OFF_SPECIAL);        // [2] tile number + 1 if irregular
+  constexpr int OFF_TBIAS = OFF_ROWINFO + 4 * BN * 4, OFF_SPECIAL = OFF_TBIAS + 16, OFF_LIST = OFF_SPECIAL + 16;
+  int* rowinfo = reinterpret_cast<int*>(smem + OFF_ROWINFO);        // [4][BN] source row, -1 = no key
+  float* tilebias = reinterpret_cast<float*>(smem + OFF_TBIAS);     // [4] level - 1
+  int* special = reinterpret_cast<int*>(smem + OFF_SPECIAL);        // [4] tile number + 1 if irregular
   uint16_t* list = reinterpret_cast<uint16_t*>(smem + OFF_LIST);    // kept block ids, level-major
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -152,38 +152,51 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     vswz[k] = (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);  // spreads 4 rows x 64 B
   }
 
-  // issue the direct-to-LDS loads of the loader's current tile into buffer `slot`, then step it
-  auto issue_tile = [&](int slot, int tileno) {
+  uint32_t voff_keep[RI];                     // row offsets of the tile whose K was issued last
+  const char* vbase_keep = nullptr;
+  // K rows of the loader's tile t -> K buffer t & 1 (plus the tile's bookkeeping), then step the loader
+  auto issue_k = [&](int t) __attribute__((always_inline)) {
     const int g0 = ld_tl << 6;
     const int thm1 = (1 << ls.lg_th) - 1;
+    const int ms = t & 3;
     bool irregular = false;
+    int jj[RI];
+#pragma unroll
+    for (int k = 0; k < RI; ++k) {                             // all block ids first: one LDS round trip
+      const int e = (g0 + r_k[k]) >> ls.lg_th;
+      jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
+    }
 #pragma unroll
     for (int k = 0; k < RI; ++k) {
       const int g = g0 + r_k[k];                               // position in the level's token stream
       const int e = g >> ls.lg_th;                             // list entry
-      const int ec = e < ls.nblk ? e : ls.nblk - 1;
-      const int j = (int)list[ls.lvl_start + ec];
-      const int prow = (j << ls.lg_th) | (g & thm1);           // row in the level-h array
+      const int prow = (jj[k] << ls.lg_th) | (g & thm1);       // row in the level-h array
       irregular |= (e >= ls.nblk) | (prow >= ls.lim);
       const int prow_c = prow < ls.rowmax ? prow : ls.rowmax;
       const uint32_t voff = (uint32_t)prow_c * (uint32_t)ROWB;
-      const int inst = k * NW + wave;
+      voff_keep[k] = voff;
       __builtin_amdgcn_global_load_lds((gbl_void*)(ls.kbase + (voff + kswz[k])),
-                                       (lds_void*)(smem + OFF_K + slot * TILEB + inst * RPI * ROWB), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gbl_void*)(ls.vbase + (voff + vswz[k])),
-                                       (lds_void*)(smem + OFF_V + slot * TILEB + inst * RPI * ROWB), 16, 0, 0);
-      if (lpos == 0) rowinfo[slot * BN + r_k[k]] = e < ls.nblk ? prow : -1;
+                                       (lds_void*)(smem + OFF_K + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB), 16, 0, 0);
+      if (lpos == 0) rowinfo[ms * BN + r_k[k]] = e < ls.nblk ? prow : -1;
     }
-    if (__any(irregular)) special[slot] = tileno + 1;
-    if (tid == 0) tilebias[slot] = (float)(ls.h - 1);
+    vbase_keep = ls.vbase;
+    if (__any(irregular)) special[ms] = t + 1;
+    if (tid == 0) tilebias[ms] = (float)(ls.h - 1);
     ++ld_tl;
     if (ld_tl >= ls.ntl) {
       ld_tl = 0;
       do { enter_level(ls.h + 1, ls.lvl_start + ls.nblk); } while (ls.h <= a.H && ls.ntl == 0);
     }
   };
+  // V rows of the tile whose K was issued last -> V buffer t & 1
+  auto issue_v = [&](int t) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < RI; ++k)
+      __builtin_amdgcn_global_load_lds((gbl_void*)(vbase_keep + (voff_keep[k] + vswz[k])),
+                                       (lds_void*)(smem + OFF_V + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB), 16, 0, 0);
+  };
 
-  if (tid == 0) { special[0] = 0; special[1] = 0; }
+  if (tid < 4) special[tid] = 0;
 
   // ---- query fragments (B operand of S^T = K Q^T): lane holds row qrow, 8 channels per k-step
   bf16x8 qf[D / 16];
@@ -204,12 +217,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     for (int v = 0; v < 16; ++v) oacc[md][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- per-lane LDS read addresses (bytes, buffer 0; XOR with TILEB flips the buffer)
-  // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ swizzle(row); the swizzle does not depend on mb
-  uint32_t kaddr[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks)
-    kaddr[ks] = (uint32_t)(OFF_K + l32 * ROWB + (((2 * ks + hf) ^ ((l32 / RP256) % CPR)) << 4));
+  // ---- per-lane LDS read addresses (bytes, buffer 0; XOR with TILEB selects buffer 1)
+  // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ swizzle(row) = chunk(ks = 0) ^ 2 ks
+  const uint32_t kaddr0 = (uint32_t)(OFF_K + l32 * ROWB + ((hf ^ ((l32 / RP256) % CPR)) << 4));
   // V^T operand through the transposing load: the 16 lanes of a group address 4 rows x 32 B; lane
   // (group g, s) receives channel md*32 + (g&1)*16 + s of the rows addressed by lanes s/4 + {0,4,8,12}
   uint32_t vaddr[D / 32];
@@ -223,57 +233,53 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       vaddr[md] = (uint32_t)(OFF_V + v_row * ROWB + (((md * 4 + v_dsel * 2 + (v_q >> 1)) ^ fv_rd) << 4) + (v_q & 1) * 8);
   }
 
-  __syncthreads();                           // block list and special[] are in LDS
-  if (total_tiles > 0) issue_tile(0, 0);
-  for (int t = 0; t < total_tiles; ++t) {
-    const int slot = t & 1;
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's loads of tile t have landed
-    __syncthreads();                          // ... and everyone else's; tile t-1 fully consumed
-    if (t + 1 < total_tiles) issue_tile(slot ^ 1, t + 1);   // overlaps with the math below
-
-    // ---- operand fetch: every K fragment of the tile and the V^T fragments of the first half of
-    //      the channels are requested from LDS up front, so the matrix pipe never waits on a
-    //      single outstanding read
-    auto read_vt = [&](int md, int ks) {
-      const unsigned char* vp = smem + vaddr[md] + ks * 16 * ROWB;
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
-      return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  // S^T = K Q^T for tile t (K buffer t & 1): two 32-row halves of the 64 key columns.  K fragments are
+  // requested KB k-steps ahead of the MFMAs that use them.
+  auto qk_tile = [&](f32x16 (&sc)[2], int t) __attribute__((always_inline)) {
+    const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
+    constexpr int KB = 4;                       // k-steps per batch
+    constexpr int NB = 2 * (D / 16) / KB;       // batches: (mb, ks-group)
+    bf16x8 kf[2][KB];
+    auto read_k = [&](int bi, int u) __attribute__((always_inline)) {
+      const int mb = bi / (NB / 2), ks = (bi % (NB / 2)) * KB + u;
+      return *reinterpret_cast<const bf16x8*>(smem + (kaddr0 ^ flip ^ (uint32_t)(ks << 5)) + mb * 32 * ROWB);
     };
-    constexpr int MDH = D / 64;              // channel blocks per half
-    bf16x8 kfr[2][D / 16];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int u = 0; u < KB; ++u) kf[0][u] = read_k(0, u);
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks)
-        kfr[mb][ks] = *reinterpret_cast<const bf16x8*>(smem + kaddr[ks] + mb * 32 * ROWB);
-    bf16x8 vfa[MDH][4];
+    for (int bi = 0; bi < NB; ++bi) {
+      if (bi + 1 < NB) {
 #pragma unroll
-    for (int md = 0; md < MDH; ++md)
+        for (int u = 0; u < KB; ++u) kf[(bi + 1) & 1][u] = read_k(bi + 1, u);
+      }
+      const int mb = bi / (NB / 2);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) vfa[md][ks] = read_vt(md, ks);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- S^T = K Q^T : two 32-row halves of the 64 key columns
-    f32x16 sacc[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
+      for (int u = 0; u < KB; ++u) {
+        const int ks = (bi % (NB / 2)) * KB + u;
         if (ks == 0) {
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[mb][ks], qf[ks], zero, 0, 0, 0);
+          sc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[ks], zero, 0, 0, 0);
         } else {
-          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[mb][ks], qf[ks], sacc[mb], 0, 0, 0);
+          sc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[ks], sc[mb], 0, 0, 0);
         }
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
+    // issue order: KB LDS reads ahead, then one read per MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);
+#pragma unroll
+    for (int i = 0; i < 2 * (D / 16) - KB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);
+  };
 
-    // ---- online softmax (log2 domain).  register v of half mb is key column
-    //      mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
-    const float tbias = tilebias[slot];
-    const bool slow = special[slot] == t + 1;
+  // online softmax (log2 domain) of tile t held in sc -> bfloat16 P^T fragments.  register v of half
+  // mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
+  auto softmax_tile = [&](f32x16 (&sc)[2], bf16x8 (&pf)[4], int t) __attribute__((always_inline)) {
+    const int ms = t & 3;
+    const float tbias = tilebias[ms];
+    const bool slow = special[ms] == t + 1;
     float tmax = -INFINITY;
     if (slow) {
       const int hm1 = (int)tbias;
@@ -283,22 +289,22 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int col = mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-          const int pr = rowinfo[slot * BN + col];
+          const int pr = rowinfo[ms * BN + col];
           const int first = pr << hm1;
           int c = a.N - first;
           c = c < 0 ? 0 : (c > span ? span : c);
           if (pr < 0) c = 0;
-          float x = sacc[mb][v] * a.scale_log2 + __log2f((float)c);   // log2(0) = -inf masks the key
+          float x = sc[mb][v] * a.scale_log2 + __log2f((float)c);   // log2(0) = -inf masks the key
           if (a.causal && first + c - 1 > qrow) x = -INFINITY;
           if (c == 0) x = -INFINITY;
-          sacc[mb][v] = x;
+          sc[mb][v] = x;
           tmax = fmaxf(tmax, x);
         }
     } else {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sacc[mb][v]);
+        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sc[mb][v]);
       tmax = tmax * a.scale_log2 + tbias;
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
@@ -313,13 +319,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       m_run = m_new;
     }
     const float m_use = m_run == -INFINITY ? 0.f : m_run;
-    bf16x8 pf[4];
     if (slow) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(sacc[mb][v] - m_use);
+          const float p = __builtin_amdgcn_exp2f(sc[mb][v] - m_use);
           l_run += p;
           pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
         }
@@ -329,36 +334,81 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][v], a.scale_log2, shift));
+          const float p = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
           l_run += p;
           pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
         }
     }
+  };
 
-    // ---- O^T += V^T P^T : contraction index (hf, e) of k-step ks is key column
-    //      ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers above
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 vfb[MDH][4];
+  // O^T += V^T P^T for tile t (V buffer t & 1): contraction index (hf, e) of k-step ks is key column
+  // ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers.  One channel block at a time, the V^T
+  // fragments of the next block requested while the current one multiplies.
+  auto pv_tile = [&](const bf16x8 (&pf)[4], int t) __attribute__((always_inline)) {
+    const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
+    auto read_vt = [&](int md, int ks) __attribute__((always_inline)) {
+      const unsigned char* vp = smem + (vaddr[md] ^ flip) + ks * 16 * ROWB;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
+      return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    bf16x8 vf[2][4];
 #pragma unroll
-    for (int md = 0; md < MDH; ++md)
+    for (int ks = 0; ks < 4; ++ks) vf[0][ks] = read_vt(0, ks);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) vfb[md][ks] = read_vt(MDH + md, ks);
+    for (int md = 0; md < D / 32; ++md) {
+      if (md + 1 < D / 32) {
 #pragma unroll
-    for (int md = 0; md < MDH; ++md)
+        for (int ks = 0; ks < 4; ++ks) vf[(md + 1) & 1][ks] = read_vt(md + 1, ks);
+      }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
-        oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfa[md][ks], pf[ks], oacc[md], 0, 0, 0);
+        oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[md & 1][ks], pf[ks], oacc[md], 0, 0, 0);
+    }
+    // issue order: the 8 transposing reads of one channel block ahead, then two reads per MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-    for (int md = 0; md < MDH; ++md)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        oacc[MDH + md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfb[md][ks], pf[ks], oacc[MDH + md], 0, 0, 0);
+    for (int i = 0; i < 4 * (D / 32 - 1); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  };
+
+  // One step per tile, software-pipelined inside the wavefront: the S^T MFMAs of tile t+1 are issued
+  // BEFORE the softmax of tile t, so the matrix pipe works through them while the vector unit does
+  // the exponentials; then P V of tile t follows.  Loads run two tiles ahead of the softmax:
+  //   step t:  wait + barrier | issue V(t+1), K(t+2) | QK(t+1) | softmax(t) | PV(t)
+  auto step = [&](f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's K(t+1), V(t) have landed
+    __syncthreads();                          // ... and everyone else's; buffers of K(t), V(t-1) are free
+    if (t + 1 < total_tiles) issue_v(t + 1);
+    if (t + 2 < total_tiles) issue_k(t + 2);
+    if (t + 1 < total_tiles) qk_tile(sn, t + 1);
     __builtin_amdgcn_sched_barrier(0);
-    // flip the LDS read addresses to the other buffer
+    bf16x8 pf[4];
+    softmax_tile(sc, pf, t);
+    __builtin_amdgcn_sched_barrier(0);
+    pv_tile(pf, t);
+  };
+
+  f32x16 sA[2], sB[2];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) kaddr[ks] ^= (uint32_t)TILEB;
+  for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int md = 0; md < D / 32; ++md) vaddr[md] ^= (uint32_t)TILEB;
+    for (int v = 0; v < 16; ++v) { sA[mb][v] = 0.f; sB[mb][v] = 0.f; }
+  __syncthreads();                           // block list and special[] are in LDS
+  if (total_tiles > 0) {
+    issue_k(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    issue_v(0);
+    if (total_tiles > 1) issue_k(1);
+    qk_tile(sA, 0);
+  }
+  for (int t = 0; t < total_tiles; t += 2) {
+    step(sA, sB, t);
+    if (t + 1 < total_tiles) step(sB, sA, t + 1);
   }
 
   // ---- epilogue: O = o / l ; lane (qrow, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
@@ -380,7 +430,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 }
 
 size_t attn_mfma_smem_bytes(int d, int nk) {
-  return 4 * (size_t)BN * d * sizeof(bf16_t) + 2 * BN * sizeof(int) + 16 + (((size_t)nk * 2 + 15) & ~(size_t)15);
+  return 4 * (size_t)BN * d * sizeof(bf16_t) + 4 * BN * sizeof(int) + 32 + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
 template <int D, int NW>
