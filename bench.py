@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--workload", default="dit1p3b", help="key of synth_inputs.CONFIGS")
     ap.add_argument("--budget", type=float, default=None, help="compute budget rho-bar (default: the workload's)")
     ap.add_argument("--levels", type=int, default=None, help="pyramid depth override (1 = binary block-sparse)")
+    ap.add_argument("--seq", type=int, default=None, help="sequence length override (shorter variant of the workload)")
+    ap.add_argument("--heads", type=int, default=None, help="query-head count override (KV heads scale along)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check-dense", action="store_true", help="also report rel-L2 of PSA vs dense attention")
     return ap.parse_args()
@@ -115,6 +117,9 @@ def main():
     w = si.CONFIGS[args.workload]
     if args.levels:
         w = w.with_(levels=args.levels)
+    if args.seq or args.heads:
+        hq = args.heads or w.Hq
+        w = si.small_variant(w, args.seq or w.N, Hq=hq, Hkv=max(1, hq * w.Hkv // w.Hq))
     budget = args.budget if args.budget is not None else w.budget
     gp = psa.make_params(w.B, w.Hq, w.Hkv, w.N, w.d, w.bq, w.bk, w.levels,
                          dtype=psa.PSA_BF16 if w.dtype == "bf16" else psa.PSA_F32, causal=w.causal,

@@ -6,7 +6,10 @@
 // b_k/2^(h-1) tokens is split over several tiles or merged with its neighbours), so every tile but
 // the last of a level feeds full 32x32x16 MFMAs and the (h-1) ln 2 bias is one constant per tile.
 //
-// One workgroup = one slice of up to 128 query rows; each wavefront owns 32 rows.  Per tile:
+// One workgroup = one slice of up to 128 query rows.  A wavefront owns QB groups of 32 rows.  QB = 2
+// lets every K / V^T fragment read from LDS feed two MFMAs (half the LDS traffic per FLOP) but needs
+// one wavefront per SIMD with a 512-register budget; measured at d = 64 it is 1.5x SLOWER than
+// QB = 1 with two wavefronts per SIMD, so QB = 1 is what the launcher picks.  Per tile:
 //   K/V rows go HBM/L2 -> LDS directly (global_load_lds, 16 B per lane), double-buffered, one
 //   barrier per tile; the 16-byte chunks of a row are XOR-swizzled on the way in so that the MFMA
 //   operand reads are bank-conflict free without padding.
@@ -15,8 +18,11 @@
 //   lane, so row max / row sum are in-lane reductions plus one exchange with lane^32, and the
 //   bfloat16 P^T fragments are already in the B-operand layout of the second product
 //   O^T += V_tile^T P^T     (A = V^T, read from the row-major V tile with the transposing LDS load)
-// The running maximum is only advanced when it grows by more than 2^8 (the accumulators stay well
-// inside fp32 range), which removes the per-tile rescale of O from the common path.
+// The step is software-pipelined inside the wavefront: the S^T MFMAs of tile t+1 are issued before
+// the softmax of tile t, so the matrix pipe works through them while the vector unit does the
+// exponentials.  The running maximum is only advanced when it grows by more than 2^8 (the
+// accumulators stay well inside fp32 range), which removes the per-tile rescale of O from the
+// common path.
 #include "psa_dev.h"
 #include "psa_internal.h"
 
@@ -52,12 +58,15 @@ struct LevelState {
   const char* vbase;
 };
 
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
-    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp, const uint16_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
+// D: head dimension; NW: wavefronts per workgroup; QB: 32-row groups per wavefront
+template <int D, int NW, int QB>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(QB == 2 ? 1 : 2, QB == 2 ? 1 : 2)))
+void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                      const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
+                      const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                      bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
   constexpr int NT = NW * 64;
+  constexpr int ROWS = NW * QB * 32;         // query rows per workgroup
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;              // tile rows covered by one wave-wide 16 B/lane load
   constexpr int NINST = BN / RPI;            // such loads per tensor per tile
@@ -92,10 +101,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
   const int hk = hq / (a.Hq / a.Hkv);
   const int64_t qhead = (int64_t)b * a.Hq + hq;
   const int64_t khead = (int64_t)b * a.Hkv + hk;
-  const int row0 = i * a.bq + slice * (NW * 32);
+  const int row0 = i * a.bq + slice * ROWS;
   int row_end = (i + 1) * a.bq;
   row_end = row_end < a.N ? row_end : a.N;
-  const int qrow = row0 + wave * 32 + l32;
+  int qrow[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) qrow[qb] = row0 + (wave * QB + qb) * 32 + l32;
 
   const int64_t srow = qhead * a.nq + i;
   const uint16_t* my_idx = idx + srow * a.nk;
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
   for (int x = tid; x < total_blocks; x += NT) list[x] = my_idx[x];
 
   LevelState ls;
-  auto enter_level = [&](int h, int lvl_start) {   // scalar work, once per level
+  auto enter_level = [&](int h, int lvl_start) __attribute__((always_inline)) {   // scalar work, once per level
     ls.h = h;
     ls.lvl_start = lvl_start;
     if (h > a.H) { ls.nblk = 0; ls.ntl = 0; return; }
@@ -198,24 +209,30 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 
   if (tid < 4) special[tid] = 0;
 
-  // ---- query fragments (B operand of S^T = K Q^T): lane holds row qrow, 8 channels per k-step
-  bf16x8 qf[D / 16];
-  {
-    const bf16_t* qp = Q + (qhead * a.N + qrow) * D + hf * 8;
+  // ---- query fragments (B operand of S^T = K Q^T): lane holds one row, 8 channels per k-step
+  bf16x8 qf[QB][D / 16];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const bf16_t* qp = Q + (qhead * a.N + qrow[qb]) * D + hf * 8;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (qrow < row_end) v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
-      qf[ks] = __builtin_bit_cast(bf16x8, v);
+      if (qrow[qb] < row_end) v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
-  f32x16 oacc[D / 32];
+  f32x16 oacc[QB][D / 32];
+  float m_run[QB], l_run[QB];
 #pragma unroll
-  for (int md = 0; md < D / 32; ++md)
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) oacc[md][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+    for (int md = 0; md < D / 32; ++md)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) oacc[qb][md][v] = 0.f;
+  }
 
   // ---- per-lane LDS read addresses (bytes, buffer 0; XOR with TILEB selects buffer 1)
   // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ swizzle(row) = chunk(ks = 0) ^ 2 ks
@@ -233,9 +250,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       vaddr[md] = (uint32_t)(OFF_V + v_row * ROWB + (((md * 4 + v_dsel * 2 + (v_q >> 1)) ^ fv_rd) << 4) + (v_q & 1) * 8);
   }
 
-  // S^T = K Q^T for tile t (K buffer t & 1): two 32-row halves of the 64 key columns.  K fragments are
-  // requested KB k-steps ahead of the MFMAs that use them.
-  auto qk_tile = [&](f32x16 (&sc)[2], int t) __attribute__((always_inline)) {
+  // S^T = K Q^T for tile t (K buffer t & 1): two 32-row halves of the 64 key columns; every K
+  // fragment feeds the MFMAs of all QB row groups.  Fragments are requested KB k-steps ahead.
+  auto qk_tile = [&](f32x16 (&sc)[QB][2], int t) __attribute__((always_inline)) {
     const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
     constexpr int KB = 4;                       // k-steps per batch
     constexpr int NB = 2 * (D / 16) / KB;       // batches: (mb, ks-group)
@@ -256,27 +273,31 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 #pragma unroll
       for (int u = 0; u < KB; ++u) {
         const int ks = (bi % (NB / 2)) * KB + u;
-        if (ks == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          sc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[ks], zero, 0, 0, 0);
-        } else {
-          sc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[ks], sc[mb], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          if (ks == 0) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            sc[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[qb][ks], zero, 0, 0, 0);
+          } else {
+            sc[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[qb][ks], sc[qb][mb], 0, 0, 0);
+          }
         }
       }
     }
-    // issue order: KB LDS reads ahead, then one read per MFMA
+    // issue order: KB LDS reads ahead, then one read per QB MFMAs
     __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);
 #pragma unroll
     for (int i = 0; i < 2 * (D / 16) - KB; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, KB, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, KB * QB, 0);
   };
 
-  // online softmax (log2 domain) of tile t held in sc -> bfloat16 P^T fragments.  register v of half
-  // mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
-  auto softmax_tile = [&](f32x16 (&sc)[2], bf16x8 (&pf)[4], int t) __attribute__((always_inline)) {
+  // online softmax (log2 domain) of one 32-row group of tile t -> bfloat16 P^T fragments.  register v
+  // of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
+  auto softmax_tile = [&](f32x16 (&sc)[2], bf16x8 (&pf)[4], f32x16 (&oa)[D / 32], float& mr, float& lr, int myrow,
+                          int t) __attribute__((always_inline)) {
     const int ms = t & 3;
     const float tbias = tilebias[ms];
     const bool slow = special[ms] == t + 1;
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
           c = c < 0 ? 0 : (c > span ? span : c);
           if (pr < 0) c = 0;
           float x = sc[mb][v] * a.scale_log2 + __log2f((float)c);   // log2(0) = -inf masks the key
-          if (a.causal && first + c - 1 > qrow) x = -INFINITY;
+          if (a.causal && first + c - 1 > myrow) x = -INFINITY;
           if (c == 0) x = -INFINITY;
           sc[mb][v] = x;
           tmax = fmaxf(tmax, x);
@@ -308,24 +329,24 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       tmax = tmax * a.scale_log2 + tbias;
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    if (__any(tmax - m_run > LAZY_RESCALE)) {
-      const float m_new = fmaxf(m_run, tmax);
-      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
+    if (__any(tmax - mr > LAZY_RESCALE)) {
+      const float m_new = fmaxf(mr, tmax);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(mr - m_new);
+      lr *= alpha;
 #pragma unroll
       for (int md = 0; md < D / 32; ++md)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[md][v] *= alpha;
-      m_run = m_new;
+        for (int v = 0; v < 16; ++v) oa[md][v] *= alpha;
+      mr = m_new;
     }
-    const float m_use = m_run == -INFINITY ? 0.f : m_run;
+    const float m_use = mr == -INFINITY ? 0.f : mr;
     if (slow) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const float p = __builtin_amdgcn_exp2f(sc[mb][v] - m_use);
-          l_run += p;
+          lr += p;
           pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
         }
     } else {
@@ -335,7 +356,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const float p = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
-          l_run += p;
+          lr += p;
           pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
         }
     }
@@ -343,8 +364,9 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
 
   // O^T += V^T P^T for tile t (V buffer t & 1): contraction index (hf, e) of k-step ks is key column
   // ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers.  One channel block at a time, the V^T
-  // fragments of the next block requested while the current one multiplies.
-  auto pv_tile = [&](const bf16x8 (&pf)[4], int t) __attribute__((always_inline)) {
+  // fragments of the next block requested while the current one multiplies; every fragment feeds the
+  // MFMAs of all QB row groups.
+  auto pv_tile = [&](const bf16x8 (&pf)[QB][4], int t) __attribute__((always_inline)) {
     const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
     auto read_vt = [&](int md, int ks) __attribute__((always_inline)) {
       const unsigned char* vp = smem + (vaddr[md] ^ flip) + ks * 16 * ROWB;
@@ -363,40 +385,42 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
       }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks)
-        oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[md & 1][ks], pf[ks], oacc[md], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          oacc[qb][md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[md & 1][ks], pf[qb][ks], oacc[qb][md], 0, 0, 0);
     }
-    // issue order: the 8 transposing reads of one channel block ahead, then two reads per MFMA
+    // issue order: the 8 transposing reads of one channel block ahead, then two reads per QB MFMAs
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
     for (int i = 0; i < 4 * (D / 32 - 1); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 4 * QB, 0);
   };
 
-  // One step per tile, software-pipelined inside the wavefront: the S^T MFMAs of tile t+1 are issued
-  // BEFORE the softmax of tile t, so the matrix pipe works through them while the vector unit does
-  // the exponentials; then P V of tile t follows.  Loads run two tiles ahead of the softmax:
-  //   step t:  wait + barrier | issue V(t+1), K(t+2) | QK(t+1) | softmax(t) | PV(t)
-  auto step = [&](f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
+  // One step per tile:  wait + barrier | issue V(t+1), K(t+2) | QK(t+1) | softmax(t) | PV(t)
+  auto step = [&](f32x16 (&sc)[QB][2], f32x16 (&sn)[QB][2], int t) __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's K(t+1), V(t) have landed
     __syncthreads();                          // ... and everyone else's; buffers of K(t), V(t-1) are free
     if (t + 1 < total_tiles) issue_v(t + 1);
     if (t + 2 < total_tiles) issue_k(t + 2);
     if (t + 1 < total_tiles) qk_tile(sn, t + 1);
     __builtin_amdgcn_sched_barrier(0);
-    bf16x8 pf[4];
-    softmax_tile(sc, pf, t);
+    bf16x8 pf[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) softmax_tile(sc[qb], pf[qb], oacc[qb], m_run[qb], l_run[qb], qrow[qb], t);
     __builtin_amdgcn_sched_barrier(0);
     pv_tile(pf, t);
   };
 
-  f32x16 sA[2], sB[2];
+  f32x16 sA[QB][2], sB[QB][2];
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+  for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { sA[mb][v] = 0.f; sB[mb][v] = 0.f; }
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sA[qb][mb][v] = 0.f; sB[qb][mb][v] = 0.f; }
   __syncthreads();                           // block list and special[] are in LDS
   if (total_tiles > 0) {
     issue_k(0);
@@ -411,21 +435,24 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_mfma_kernel(
     if (t + 1 < total_tiles) step(sB, sA, t + 1);
   }
 
-  // ---- epilogue: O = o / l ; lane (qrow, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (qrow < row_end) {
-    const float inv = 1.f / l_tot;
-    bf16_t* op = O + (qhead * a.N + qrow) * D;
+  // ---- epilogue: O = o / l ; lane (row, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
 #pragma unroll
-    for (int md = 0; md < D / 32; ++md)
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+    if (qrow[qb] < row_end) {
+      const float inv = 1.f / l_tot;
+      bf16_t* op = O + (qhead * a.N + qrow[qb]) * D;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 w;
+      for (int md = 0; md < D / 32; ++md)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[md][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + md * 32 + g * 8 + hf * 4) = w;
-      }
-    if (lse && hf == 0) lse[qhead * a.N + qrow] = (m_run + __log2f(l_tot)) * 0.69314718055994531f;
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[qb][md][4 * g + e] * inv);
+          *reinterpret_cast<bf16x4*>(op + md * 32 + g * 8 + hf * 4) = w;
+        }
+      if (lse && hf == 0) lse[qhead * a.N + qrow[qb]] = (m_run[qb] + __log2f(l_tot)) * 0.69314718055994531f;
+    }
   }
 }
 
@@ -433,7 +460,7 @@ size_t attn_mfma_smem_bytes(int d, int nk) {
   return 4 * (size_t)BN * d * sizeof(bf16_t) + 4 * BN * sizeof(int) + 32 + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
-template <int D, int NW>
+template <int D, int NW, int QB>
 static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                                 const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                                 hipStream_t s) {
@@ -442,12 +469,13 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.H = pl.H; a.causal = pl.causal;
   a.lg_bk = 0;
   while ((1 << a.lg_bk) < pl.bk) ++a.lg_bk;
-  a.slices = (pl.bq + NW * 32 - 1) / (NW * 32);
+  constexpr int ROWS = NW * QB * 32;
+  a.slices = (pl.bq + ROWS - 1) / ROWS;
   a.items = pl.B * pl.Hq * pl.nq * a.slices;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
   const size_t smem = attn_mfma_smem_bytes(D, pl.nk);
-  auto kern = attn_mfma_kernel<D, NW>;
+  auto kern = attn_mfma_kernel<D, NW, QB>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)smem);
   if (e != hipSuccess) return e;
@@ -461,18 +489,17 @@ hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const 
                             const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                             hipStream_t s) {
   const int rows = pl.bq < 128 ? pl.bq : 128;   // rows per workgroup
-  const int nw = rows / 32;
   if (pl.d == 128) {
-    switch (nw) {
-      case 1: return launch_mfma_t<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 2: return launch_mfma_t<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 4: return launch_mfma_t<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+    switch (rows) {
+      case 32: return launch_mfma_t<128, 1, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_t<128, 2, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_t<128, 4, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   } else if (pl.d == 64) {
-    switch (nw) {
-      case 1: return launch_mfma_t<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 2: return launch_mfma_t<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 4: return launch_mfma_t<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+    switch (rows) {
+      case 32: return launch_mfma_t<64, 1, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_t<64, 2, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_t<64, 4, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   }
   return hipErrorInvalidValue;
