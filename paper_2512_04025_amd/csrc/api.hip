@@ -8,6 +8,7 @@
 namespace psa {
 
 size_t importance_smem_bytes(int sq, int nk, int d);
+bool importance_uses_mfma(const Plan& pl);
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -149,7 +150,7 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
   if (!scores_in) {
     if (!Q) return PSA_EINVAL;
     if (pl.krep_is_pyramid ? !Kpyr : !K) return PSA_EINVAL;
-    if (importance_smem_bytes(pl.sq, pl.nk, pl.d) > LDS_LIMIT) return PSA_EUNSUPPORTED;
+    if (!importance_uses_mfma(pl) && importance_smem_bytes(pl.sq, pl.nk, pl.d) > LDS_LIMIT) return PSA_EUNSUPPORTED;
     void* qrep = at(scratch, pl.off_qrep);
     const void* krep;
     if (launch_representatives(pl, Q, qrep, true, s) != hipSuccess) return PSA_ELAUNCH;
