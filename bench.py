@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--levels", type=int, default=None, help="pyramid depth override (1 = binary block-sparse)")
     ap.add_argument("--seq", type=int, default=None, help="sequence length override (shorter variant of the workload)")
     ap.add_argument("--heads", type=int, default=None, help="query-head count override (KV heads scale along)")
+    ap.add_argument("--copy-probe-mb", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check-dense", action="store_true", help="also report rel-L2 of PSA vs dense attention")
     return ap.parse_args()
@@ -138,6 +140,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_probe_mb:
+        src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):

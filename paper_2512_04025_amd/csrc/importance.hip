@@ -217,7 +217,7 @@ static hipError_t launch_imp_t(const Plan& pl, const void* Qrep, const void* Kre
 
 // ------------------------------------------------------------------------------------------------
 // Matrix-core version for bfloat16 with 8 representatives per query block and per key block (the
-// default: pooled keys are pyramid level H).  One workgroup = 32 representative query rows (4 query
+// default: pooled keys are pyramid level H).  One workgroup = 64 representative query rows (8 query
 // blocks); its 4 wavefronts split the representative keys into 4 contiguous ranges.  The logits are
 // computed as S^T = K~ Q~^T with 32x32x16 MFMAs, so a lane holds ONE query row and, per 32-key MFMA
 // block, 16 logits = 4 key blocks x 4 keys (the other 4 keys of each block sit in lane^32).
@@ -236,25 +236,30 @@ __global__ __launch_bounds__(256) void importance_mfma_kernel(const bf16_t* __re
                                                               const bf16_t* __restrict__ Krep,
                                                               float* __restrict__ S, ImpMfmaArgs a) {
   constexpr int SQ = 8, SK = 8, KS = D / 16;
-  __shared__ float part[4][32][2];                 // per wavefront: row max (log2 domain), row sum
+  constexpr int QB = 2;                            // 32-row groups per wavefront: every K~ fragment feeds QB MFMAs
+  __shared__ float part[4][QB][32][2];             // per wavefront: row max (log2 domain), row sum
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int rg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int hk = hq / (a.Hq / a.Hkv);
   const int nrows = a.nq * SQ, nkeys = a.nk * SK;
-  const int row = rg * 32 + l32;                   // representative query row of this lane
-  const int qi = row / SQ;                         // its query block
-  const int qpos = row < nrows ? rep_pos(a.mode, qi, row % SQ, a.bq, SQ, a.N) : -1;
   const bf16_t* qbase = Qrep + (((int64_t)b * a.Hq + hq) * nrows) * D;
   const bf16_t* kbase = Krep + (((int64_t)b * a.Hkv + hk) * (int64_t)nkeys) * D;
 
-  bf16x8 qf[KS];
+  int row[QB], qi[QB], qpos[QB];
+  bf16x8 qf[QB][KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < nrows) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)row * D + ks * 16 + hf * 8);
-    qf[ks] = __builtin_bit_cast(bf16x8, v);
+  for (int qb = 0; qb < QB; ++qb) {
+    row[qb] = (rg * QB + qb) * 32 + l32;           // representative query row of this lane
+    qi[qb] = row[qb] / SQ;                         // its query block
+    qpos[qb] = row[qb] < nrows ? rep_pos(a.mode, qi[qb], row[qb] % SQ, a.bq, SQ, a.N) : -1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (row[qb] < nrows) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)row[qb] * D + ks * 16 + hf * 8);
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, v);
+    }
   }
 
   // this wavefront's range of 32-key MFMA blocks
@@ -270,47 +275,64 @@ __global__ __launch_bounds__(256) void importance_mfma_kernel(const bf16_t* __re
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + ks * 16));
   };
-  // logits of one MFMA block in the log2 domain, masked; t[v] is key blk*32 + (v/4)*8 + hf*4 + v%4
-  auto logits = [&](const bf16x8 (&kf)[KS], int blk, float (&t)[16]) __attribute__((always_inline)) {
-    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // logits of one MFMA block in the log2 domain, masked; t[qb][v] is key blk*32 + (v/4)*8 + hf*4 + v%4
+  auto logits = [&](const bf16x8 (&kf)[KS], int blk, float (&t)[QB][16]) __attribute__((always_inline)) {
+    f32x16 acc[QB];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], acc, 0, 0, 0);
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], zero, 0, 0, 0);
+        } else {
+          acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], acc[qb], 0, 0, 0);
+        }
+      }
     const int gk = a.bk / SK;
     // fast path: every key of the block is valid and nothing is causally hidden
     const bool plain = !a.causal && (a.mode == PSA_REP_STRIDED ? blk * 32 + 32 <= nkeys
                                                                : (int64_t)(blk * 32 + 31) * gk < a.N);
-    if (plain) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) t[v] = qpos >= 0 ? acc[v] * a.scale_log2 : -INFINITY;
-    } else {
+    for (int qb = 0; qb < QB; ++qb) {
+      if (plain) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int c = blk * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-        const int kpos = c < nkeys ? rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N) : -1;
-        const bool dead = kpos < 0 || qpos < 0 || (a.causal && kpos > qpos);
-        t[v] = dead ? -INFINITY : acc[v] * a.scale_log2;
+        for (int v = 0; v < 16; ++v) t[qb][v] = qpos[qb] >= 0 ? acc[qb][v] * a.scale_log2 : -INFINITY;
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int c = blk * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+          const int kpos = c < nkeys ? rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N) : -1;
+          const bool dead = kpos < 0 || qpos[qb] < 0 || (a.causal && kpos > qpos[qb]);
+          t[qb][v] = dead ? -INFINITY : acc[qb][v] * a.scale_log2;
+        }
       }
     }
   };
 
   // ---- sweep 1: row max and row sum (online, in the log2 domain)
-  float m = -INFINITY, l = 0.f;
+  float m[QB], l[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
   {
     bf16x8 ka[KS], kb[KS];
     auto stat = [&](const bf16x8 (&kf)[KS], int blk) __attribute__((always_inline)) {
-      float t[16];
+      float t[QB][16];
       logits(kf, blk, t);
-      float bm = t[0];
 #pragma unroll
-      for (int v = 1; v < 16; ++v) bm = fmaxf(bm, t[v]);
-      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-      const float mn = fmaxf(m, bm);
-      if (mn != -INFINITY) {
-        float sum = 0.f;
+      for (int qb = 0; qb < QB; ++qb) {
+        float bm = t[qb][0];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(t[v] - mn);
-        l = l * __builtin_amdgcn_exp2f(m - mn) + sum;
-        m = mn;
+        for (int v = 1; v < 16; ++v) bm = fmaxf(bm, t[qb][v]);
+        bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+        const float mn = fmaxf(m[qb], bm);
+        if (mn != -INFINITY) {
+          float sum = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(t[qb][v] - mn);
+          l[qb] = l[qb] * __builtin_amdgcn_exp2f(m[qb] - mn) + sum;
+          m[qb] = mn;
+        }
       }
     };
     if (blk_lo < blk_hi) load_k(ka, blk_lo);
@@ -323,48 +345,57 @@ __global__ __launch_bounds__(256) void importance_mfma_kernel(const bf16_t* __re
       }
     }
   }
-  l += __shfl_xor(l, 32, 64);                      // the two lane halves saw different keys
-  if (hf == 0) { part[wave][l32][0] = m; part[wave][l32][1] = l; }
-  __syncthreads();
-  float mrow = -INFINITY, lrow = 0.f;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) mrow = fmaxf(mrow, part[w][l32][0]);
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    const float mw = part[w][l32][0];
-    if (mw != -INFINITY) lrow += part[w][l32][1] * __builtin_amdgcn_exp2f(mw - mrow);
+  for (int qb = 0; qb < QB; ++qb) {
+    l[qb] += __shfl_xor(l[qb], 32, 64);            // the two lane halves saw different keys
+    if (hf == 0) { part[wave][qb][l32][0] = m[qb]; part[wave][qb][l32][1] = l[qb]; }
   }
-  const float inv_l = lrow > 0.f ? 1.f / lrow : 0.f;
-  const float m_use = mrow == -INFINITY ? 0.f : mrow;
+  __syncthreads();
+  float inv_l[QB], m_use[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    float mrow = -INFINITY, lrow = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) mrow = fmaxf(mrow, part[w][qb][l32][0]);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = part[w][qb][l32][0];
+      if (mw != -INFINITY) lrow += part[w][qb][l32][1] * __builtin_amdgcn_exp2f(mw - mrow);
+    }
+    inv_l[qb] = lrow > 0.f ? 1.f / lrow : 0.f;
+    m_use[qb] = mrow == -INFINITY ? 0.f : mrow;
+  }
 
   // ---- sweep 2: normalised weights reduced to one score per (query block, key block)
   float* out = S + (((int64_t)b * a.Hq + hq) * a.nq) * (int64_t)a.nk;
   {
     bf16x8 ka[KS], kb[KS];
     auto emit = [&](const bf16x8 (&kf)[KS], int blk) __attribute__((always_inline)) {
-      float t[16];
+      float t[QB][16];
       logits(kf, blk, t);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {                // key block blk*4 + g: 4 keys here, 4 in lane^32
-        float r;
-        if (a.est_pool == PSA_EST_MAX) {
-          r = fmaxf(fmaxf(t[4 * g], t[4 * g + 1]), fmaxf(t[4 * g + 2], t[4 * g + 3]));
-          r = fmaxf(r, __shfl_xor(r, 32, 64));
-          r = __builtin_amdgcn_exp2f(r - m_use) * inv_l;
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-          for (int off = 1; off < SQ; off <<= 1) r = fmaxf(r, __shfl_xor(r, off, 64));
-        } else {
-          r = __builtin_amdgcn_exp2f(t[4 * g] - m_use) + __builtin_amdgcn_exp2f(t[4 * g + 1] - m_use) +
-              __builtin_amdgcn_exp2f(t[4 * g + 2] - m_use) + __builtin_amdgcn_exp2f(t[4 * g + 3] - m_use);
-          r += __shfl_xor(r, 32, 64);
-          r *= inv_l;
+        for (int g = 0; g < 4; ++g) {              // key block blk*4 + g: 4 keys here, 4 in lane^32
+          float r;
+          if (a.est_pool == PSA_EST_MAX) {
+            r = fmaxf(fmaxf(t[qb][4 * g], t[qb][4 * g + 1]), fmaxf(t[qb][4 * g + 2], t[qb][4 * g + 3]));
+            r = fmaxf(r, __shfl_xor(r, 32, 64));
+            r = __builtin_amdgcn_exp2f(r - m_use[qb]) * inv_l[qb];
 #pragma unroll
-          for (int off = 1; off < SQ; off <<= 1) r += __shfl_xor(r, off, 64);
-          r *= 1.f / (float)(SQ * SK);
+            for (int off = 1; off < SQ; off <<= 1) r = fmaxf(r, __shfl_xor(r, off, 64));
+          } else {
+            r = __builtin_amdgcn_exp2f(t[qb][4 * g] - m_use[qb]) + __builtin_amdgcn_exp2f(t[qb][4 * g + 1] - m_use[qb]) +
+                __builtin_amdgcn_exp2f(t[qb][4 * g + 2] - m_use[qb]) + __builtin_amdgcn_exp2f(t[qb][4 * g + 3] - m_use[qb]);
+            r += __shfl_xor(r, 32, 64);
+            r *= inv_l[qb];
+#pragma unroll
+            for (int off = 1; off < SQ; off <<= 1) r += __shfl_xor(r, off, 64);
+            r *= 1.f / (float)(SQ * SK);
+          }
+          const int j = blk * 4 + g;
+          if (hf == 0 && (l32 & (SQ - 1)) == 0 && qi[qb] < a.nq && j < a.nk) out[(int64_t)qi[qb] * a.nk + j] = r;
         }
-        const int j = blk * 4 + g;
-        if (hf == 0 && (l32 & (SQ - 1)) == 0 && qi < a.nq && j < a.nk) out[(int64_t)qi * a.nk + j] = r;
-      }
     };
     if (blk_lo < blk_hi) load_k(ka, blk_lo);
     for (int blk = blk_lo; blk < blk_hi; blk += 2) {
@@ -384,7 +415,7 @@ static hipError_t launch_imp_mfma_t(const Plan& pl, const void* Qrep, const void
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.mode = pl.rep_mode; a.causal = pl.causal; a.est_pool = pl.est_pool;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
-  dim3 grid((pl.nq * 8 + 31) / 32, pl.Hq, pl.B);
+  dim3 grid((pl.nq * 8 + 63) / 64, pl.Hq, pl.B);
   importance_mfma_kernel<D><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), S, a);
   return hipGetLastError();
 }
