@@ -68,6 +68,19 @@ def pyramid_bytes(w, levels: int) -> float:
     return 2.0 * w.B * w.Hkv * w.N * w.d * e * frac
 
 
+def measured_traffic(w, budget, kernel_prefix: str):
+    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary for this exact
+    workload and budget (FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel calibration); None otherwise."""
+    path = os.path.join(ROOT, "profiles", f"psa_fwd_{w.name}_budget{budget}_traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    for name, v in rec["kernels"].items():
+        if name.startswith(kernel_prefix):
+            return v["read_bytes"] + v["write_bytes"]
+    return None
+
+
 def cpu_baseline(w, budget, Q, K, V, n_qblocks: int = 128):
     """The oracle as it stands on this host: one head's pyramid, importance and allocation, and the
     attention of a few query blocks of that head; extrapolated to the whole workload."""
@@ -183,11 +196,13 @@ def main():
         "achieved_rho": rho, "kv_coverage": coverage,
         "executed_tflop": fl_exec / 1e12, "dense_tflop": fl_dense / 1e12,
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic(w, budget, "psa::attn_mfma_kernel"),
                      "note": "executed FLOPs / mean HIP-event time of psa_attention_fwd (includes its block-list kernel)"},
         "roofline_pyramid": None if pyr_gbs is None else {
             "kernel": "pyramid_kernel", "bound": "hbm", "achieved": pyr_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": None},
+            "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": measured_traffic(w, budget, "psa::pyramid_kernel"),
+            "algorithmic_bytes": pyramid_bytes(w, w.levels)},
     }
     if w.dtype != "bf16":
         out["roofline"]["note"] += "; fp32 mode runs on the VALU (correctness mode), bf16 MFMA peak shown for scale only"

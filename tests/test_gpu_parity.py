@@ -308,3 +308,60 @@ def test_calls_are_deterministic():
         outs.append((r.buf.M.clone(), r.buf.O.clone()))
     assert torch.equal(outs[0][0], outs[1][0])
     assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+
+
+# ------------------------------------------------------------------------------- full benchmark sizes
+@pytest.mark.parametrize("key,heads", [("dit1p3b", (0, 7)), ("vlm_prefill", (5, 27))])
+def test_full_size_workload_on_sampled_query_blocks(key, heads):
+    """The configuration bench.py times, at full size: the whole path runs on the GPU; the oracle
+    recomputes scores and level maps of two heads and the attention of a sample of their query blocks
+    (first, last/ragged, causal-heavy and spread ones).  Output parity is checked with the oracle's
+    level map fed to the attention call for those heads."""
+    import torch
+    w = si.CONFIGS[key]
+    op = oracle_params(w)
+    gp = gpu_params(op)
+    Q, K, V = si.generate_qkv(w)
+    Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
+    buf = Buffers(gp)
+    psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+    psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, scores_out=buf.S, rho_out=buf.rho)
+    torch.cuda.synchronize()
+    group = w.Hq // w.Hkv
+    qblocks = sorted({0, 1, op.nq // 3, op.nq // 2, op.nq - 2, op.nq - 1})
+    M_dev = buf.M.clone()
+    refs = {}
+    for hq in heads:
+        hk = hq // group
+        op1 = oracle_params(w, B=1, Hq=1, Hkv=1)
+        Q1 = si.to_f64(Q[:1, hq:hq + 1], w.dtype)
+        K1 = si.to_f64(K[:1, hk:hk + 1], w.dtype)
+        V1 = si.to_f64(V[:1, hk:hk + 1], w.dtype)
+        S1 = orc.importance(Q1, K1, op1)
+        M1 = orc.allocate_levels(S1, op1)
+        got_S = buf.S[0, hq].cpu().numpy().astype(np.float64)
+        np.testing.assert_allclose(got_S, S1[0, 0].astype(np.float64), rtol=1e-3, atol=1e-9)
+        got_M = buf.M[0, hq].cpu().numpy()
+        assert np.mean(got_M != M1[0, 0]) <= 2e-2
+        rho = orc.compute_ratio(M1, op1)[0, 0]
+        assert abs(float(buf.rho[0, hq]) - rho) <= 2e-3
+        assert abs(rho - w.budget) <= 0.012          # Eq. 9 meets the budget (block quotas floor)
+        M_dev[0, hq] = torch.from_numpy(M1[0, 0]).cuda()
+        Kp, Vp = orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1)
+        # pyramid parity on the last (ragged) blocks of every level
+        for h in range(2, op.levels + 1):
+            t = op.tokens_per_block(h)
+            got = from_dev(buf.level(buf.Kpyr, h)[0, hk, -4 * t:], w.dtype)
+            assert np.all(np.abs(got - Kp[h][0, 0, -4 * t:]) <= _ulp(Kp[h][0, 0, -4 * t:], w.dtype))
+        O1, _ = orc.psa_attention(Q1, Kp, Vp, M1, op1, q_blocks=qblocks)
+        refs[hq] = O1[0, 0]
+    psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, M_dev, buf.O, buf.scratch)
+    torch.cuda.synchronize()
+    for hq in heads:
+        for i in qblocks:
+            rows = slice(i * w.bq, min((i + 1) * w.bq, w.N))
+            got = from_dev(buf.O[0, hq, rows], w.dtype)
+            ref = refs[hq][rows]
+            assert np.all(np.isfinite(got))
+            assert np.abs(got - ref).max() <= 2e-2, (hq, i, np.abs(got - ref).max())
+            assert rel_l2(got, ref) <= 1e-2, (hq, i, rel_l2(got, ref))
