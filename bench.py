@@ -81,7 +81,7 @@ def measured_traffic(w, budget, kernel_prefix: str):
     return None
 
 
-def cpu_baseline(w, budget, Q, K, V, n_qblocks: int = 128):
+def cpu_baseline(w, budget, Q, K, V, n_heads: int = 2):
     """The oracle as it stands on this host: one head's pyramid, importance and allocation, and the
     attention of a few query blocks of that head; extrapolated to the whole workload."""
     import dataclasses
@@ -91,18 +91,25 @@ def cpu_baseline(w, budget, Q, K, V, n_qblocks: int = 128):
     from tests.psa_testlib import oracle_params
     op = oracle_params(w, budget=budget)
     op1 = dataclasses.replace(op, B=1, Hq=1, Hkv=1)
-    Q1 = si.to_f64(Q[:1, :1], w.dtype)
-    K1 = si.to_f64(K[:1, :1], w.dtype)
-    V1 = si.to_f64(V[:1, :1], w.dtype)
-    t0 = time.perf_counter()
-    Kp, Vp = orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1)
-    t1 = time.perf_counter()
-    M = orc.allocate_levels(orc.importance(Q1, K1, op1), op1)
-    t2 = time.perf_counter()
-    qb = sorted(set(np.linspace(0, op1.nq - 1, n_qblocks).astype(int).tolist()))
-    orc.psa_attention(Q1, Kp, Vp, M, op1, q_blocks=qb)
-    t3 = time.perf_counter()
-    full = (t1 - t0) * w.B * w.Hkv + (t2 - t1) * w.B * w.Hq + (t3 - t2) / len(qb) * op.nq * w.B * w.Hq
+    group = w.Hq // w.Hkv
+    n_heads = min(n_heads, w.Hq)
+    t_pyr = t_alloc = t_attn = 0.0
+    for hq in range(n_heads):
+        hk = hq // group
+        Q1 = si.to_f64(Q[:1, hq:hq + 1], w.dtype)
+        K1 = si.to_f64(K[:1, hk:hk + 1], w.dtype)
+        V1 = si.to_f64(V[:1, hk:hk + 1], w.dtype)
+        t0 = time.perf_counter()
+        Kp, Vp = orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1)
+        t1 = time.perf_counter()
+        M = orc.allocate_levels(orc.importance(Q1, K1, op1), op1)
+        t2 = time.perf_counter()
+        orc.psa_attention(Q1, Kp, Vp, M, op1)
+        t3 = time.perf_counter()
+        t_pyr += t1 - t0
+        t_alloc += t2 - t1
+        t_attn += t3 - t2
+    full = (t_pyr * w.Hkv + (t_alloc + t_attn) * w.Hq) * w.B / n_heads
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
@@ -111,8 +118,8 @@ def cpu_baseline(w, budget, Q, K, V, n_qblocks: int = 128):
     return {
         "value": dense_flops(w) / full / 1e12, "unit": "TFLOP/s (dense-equivalent, extrapolated)",
         "cores": int(cores), "kind": "oracle",
-        "sample": f"1 of {w.B * w.Hq} heads: pyramid {t1 - t0:.2f}s, importance+allocation {t2 - t1:.2f}s, "
-                  f"attention of {len(qb)} of {op.nq} query blocks {t3 - t2:.2f}s; "
+        "sample": f"{n_heads} of {w.B * w.Hq} heads, every query block: pyramid {t_pyr:.2f}s, "
+                  f"importance+allocation {t_alloc:.2f}s, attention {t_attn:.2f}s; "
                   f"extrapolated whole-workload time {full:.1f}s",
         "ms_per_step_extrapolated": full * 1e3,
     }

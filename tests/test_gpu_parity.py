@@ -311,14 +311,26 @@ def test_calls_are_deterministic():
 
 
 # ------------------------------------------------------------------------------- full benchmark sizes
-@pytest.mark.parametrize("key,heads", [("dit1p3b", (0, 7)), ("vlm_prefill", (5, 27))])
+def _full_workload(key):
+    """Benchmark-size workloads; the two largest keep their full sequence length, block sizes and
+    level count but fewer heads (the oracle side and host-side generation stay within seconds)."""
+    C = si.CONFIGS
+    if key == "dit14b_2heads":
+        return si.small_variant(C["dit14b"], C["dit14b"].N, Hq=2, Hkv=2)
+    if key == "stress_1head":
+        return si.small_variant(C["stress"], C["stress"].N, Hq=1, Hkv=1, B=1)
+    return C[key]
+
+
+@pytest.mark.parametrize("key,heads", [("dit1p3b", (0, 7)), ("vlm_prefill", (5, 27)), ("dit14b_2heads", (1,)),
+                                       ("stress_1head", (0,))])
 def test_full_size_workload_on_sampled_query_blocks(key, heads):
     """The configuration bench.py times, at full size: the whole path runs on the GPU; the oracle
     recomputes scores and level maps of two heads and the attention of a sample of their query blocks
     (first, last/ragged, causal-heavy and spread ones).  Output parity is checked with the oracle's
     level map fed to the attention call for those heads."""
     import torch
-    w = si.CONFIGS[key]
+    w = _full_workload(key)
     op = oracle_params(w)
     gp = gpu_params(op)
     Q, K, V = si.generate_qkv(w)
@@ -365,3 +377,35 @@ def test_full_size_workload_on_sampled_query_blocks(key, heads):
             assert np.all(np.isfinite(got))
             assert np.abs(got - ref).max() <= 2e-2, (hq, i, np.abs(got - ref).max())
             assert rel_l2(got, ref) <= 1e-2, (hq, i, rel_l2(got, ref))
+
+
+def test_pyramid_levels_beat_binary_mask_at_equal_budget():
+    """Direction of the paper's Fig. 1 / Table 4 claim on synthetic data, GPU results only: at the same
+    FLOP budget the multi-level mask is closer to dense attention than the binary (H = 1) mask, and
+    the error falls as the budget grows.  Dense attention = the same kernel with M == 1."""
+    import torch
+    base = si.small_variant(si.CONFIGS["stress"], 8192, Hq=2, Hkv=2, B=1)
+    Q, K, V = si.generate_qkv(base)
+    Qd, Kd, Vd = (to_dev(x, base.dtype) for x in (Q, K, V))
+
+    def run(levels, budget, ones=False):
+        w = base.with_(levels=levels)
+        gp = gpu_params(oracle_params(w, budget=budget, sq=8, sk=8))   # same estimator for both masks
+        buf = Buffers(gp)
+        psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+        psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho)
+        if ones:
+            buf.M.fill_(1)
+        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)
+        torch.cuda.synchronize()
+        return from_dev(buf.O, "bf16"), float(buf.rho.mean())
+
+    dense, _ = run(1, 1.0, ones=True)
+    errs = {}
+    for levels in (5, 1):
+        for budget in (0.1, 0.3):
+            out, rho = run(levels, budget)
+            assert rho <= budget + 1e-3
+            errs[(levels, budget)] = rel_l2(out, dense)
+    assert errs[(5, 0.1)] < errs[(1, 0.1)] and errs[(5, 0.3)] < errs[(1, 0.3)]
+    assert errs[(5, 0.3)] < errs[(5, 0.1)] and errs[(1, 0.3)] < errs[(1, 0.1)]
