@@ -23,6 +23,8 @@
 // exponentials.  The running maximum is only advanced when it grows by more than 2^8 (the
 // accumulators stay well inside fp32 range), which removes the per-tile rescale of O from the
 // common path.
+#include <type_traits>
+
 #include "psa_dev.h"
 #include "psa_internal.h"
 
@@ -39,9 +41,10 @@ struct MfmaArgs {
 
 constexpr int BN = 64;     // key columns per tile
 constexpr float LAZY_RESCALE = 8.0f;
+// word 3 of a raw (untyped, stride 0) buffer descriptor on gfx9-family targets: 32-bit data format
+constexpr int RSRC_FLAGS = 0x00020000;
 
 typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
@@ -58,15 +61,15 @@ struct LevelState {
   const char* vbase;
 };
 
-// D: head dimension; NW: wavefronts per workgroup; QB: 32-row groups per wavefront
-template <int D, int NW, int QB>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(QB == 2 ? 1 : 2, QB == 2 ? 1 : 2)))
+// D: head dimension; NW: wavefronts per workgroup (each owns 32 query rows)
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                       const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
                       const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
                       bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
   constexpr int NT = NW * 64;
-  constexpr int ROWS = NW * QB * 32;         // query rows per workgroup
+  constexpr int ROWS = NW * 32;              // query rows per workgroup
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;              // tile rows covered by one wave-wide 16 B/lane load
   constexpr int NINST = BN / RPI;            // such loads per tensor per tile
@@ -74,14 +77,15 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   constexpr int RP256 = 16 / CPR;            // rows per 256 bytes of LDS
   constexpr int ROWB = D * 2;                // bytes per row
   constexpr int TILEB = BN * ROWB;           // bytes per tile (a power of two)
+  constexpr int NA = 2 * (D / 16);           // MFMAs of S^T = K Q^T per tile
+  constexpr int NB = 4 * (D / 32);           // MFMAs of O^T += V^T P^T per tile
+  constexpr int EPC = 32 / NA;               // softmax elements handled next to one MFMA of the first product
+  constexpr int MPC = 16 / NB;               // 3-input maxima handled next to one MFMA of the second product
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-  // LDS map: K[2] | V[2] | rowinfo[4][64] | tilebias[4] | special[4] | block list
+  static_assert(EPC * NA == 32 && MPC * NB == 16 && EPC % 2 == 0, "chunking of the softmax work");
+  // LDS map: K[2] | V[2] | block list
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_ROWINFO = 4 * TILEB;
-  constexpr int OFF_TBIAS = OFF_ROWINFO + 4 * BN * 4, OFF_SPECIAL = OFF_TBIAS + 16, OFF_LIST = OFF_SPECIAL + 16;
-  int* rowinfo = reinterpret_cast<int*>(smem + OFF_ROWINFO);        // [4][BN] source row, -1 = no key
-  float* tilebias = reinterpret_cast<float*>(smem + OFF_TBIAS);     // [4] level - 1
-  int* special = reinterpret_cast<int*>(smem + OFF_SPECIAL);        // [4] tile number + 1 if irregular
+  constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_LIST = 4 * TILEB;
   uint16_t* list = reinterpret_cast<uint16_t*>(smem + OFF_LIST);    // kept block ids, level-major
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -104,9 +108,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int row0 = i * a.bq + slice * ROWS;
   int row_end = (i + 1) * a.bq;
   row_end = row_end < a.N ? row_end : a.N;
-  int qrow[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) qrow[qb] = row0 + (wave * QB + qb) * 32 + l32;
+  const int qrow = row0 + wave * 32 + l32;
 
   const int64_t srow = qhead * a.nq + i;
   const uint16_t* my_idx = idx + srow * a.nk;
@@ -146,7 +148,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       ls.vbase = reinterpret_cast<const char*>(Vp + a.lvl_off[h] + khead * rows_h * D);
     }
   };
-  int ld_tl = 0;                              // loader's tile index inside its level
+  int ld_tl = 0;                              // planner's tile index inside its level
   enter_level(1, 0);
   while (ls.h <= a.H && ls.ntl == 0) enter_level(ls.h + 1, ls.lvl_start + ls.nblk);
 
@@ -163,76 +165,112 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     vswz[k] = (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);  // spreads 4 rows x 64 B
   }
 
-  uint32_t voff_keep[RI];                     // row offsets of the tile whose K was issued last
-  const char* vbase_keep = nullptr;
-  // K rows of the loader's tile t -> K buffer t & 1 (plus the tile's bookkeeping), then step the loader
-  auto issue_k = [&](int t) __attribute__((always_inline)) {
+  // The loader works in two stages.  PLAN (arithmetic only, besides block ids read from the list in
+  // LDS): byte offset of the source row of each tile row, and two facts about the tile that every
+  // wavefront derives for itself and queues in scalar registers for the softmax three tiles later:
+  // its level, and whether it is irregular (see fixup_special).  FIRE: the direct-to-LDS loads of a
+  // planned tile.  Plans run ahead of the loads so that their arithmetic sits between the MFMAs of the
+  // second product.
+  //   planK: offsets of the tile whose K rows go out next; planV: tile whose V rows go out next
+  uint32_t planK[RI], planV[RI];
+  const char *planK_kbase = nullptr, *planK_vbase = nullptr, *planV_vbase = nullptr;
+  int plan_jj[RI];
+  bool plan_irregular = false;
+  uint32_t lvl_ring = 0, spec_ring = 0;       // per tile mod 8: 4 bits of level - 1; 1 bit irregular
+  constexpr int LG_RPI = RPI == 4 ? 2 : (RPI == 8 ? 3 : -1);
+  static_assert(LG_RPI > 0, "rows per load instruction");
+  const uint32_t lane_rowoff = (uint32_t)(lrow * ROWB);
+  // A level whose pooled blocks hold at least RPI rows: each load instruction stays inside one block,
+  // so the block id and the row offset are wave-uniform and computed on the scalar unit.
+  auto plan_begin = [&]() __attribute__((always_inline)) {
     const int g0 = ld_tl << 6;
-    const int thm1 = (1 << ls.lg_th) - 1;
-    const int ms = t & 3;
-    bool irregular = false;
-    int jj[RI];
-#pragma unroll
-    for (int k = 0; k < RI; ++k) {                             // all block ids first: one LDS round trip
-      const int e = (g0 + r_k[k]) >> ls.lg_th;
-      jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
+    {  // the whole tile, one row per lane: is any row past the kept blocks, the ragged tail or the causal limit?
+      const int g = g0 + lane, e = g >> ls.lg_th;
+      const int jl = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
+      const int prow = (jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
+      plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
     }
+    if (ls.lg_th >= LG_RPI) {
 #pragma unroll
-    for (int k = 0; k < RI; ++k) {
-      const int g = g0 + r_k[k];                               // position in the level's token stream
-      const int e = g >> ls.lg_th;                             // list entry
-      const int prow = (jj[k] << ls.lg_th) | (g & thm1);       // row in the level-h array
-      irregular |= (e >= ls.nblk) | (prow >= ls.lim);
-      const int prow_c = prow < ls.rowmax ? prow : ls.rowmax;
-      const uint32_t voff = (uint32_t)prow_c * (uint32_t)ROWB;
-      voff_keep[k] = voff;
-      __builtin_amdgcn_global_load_lds((gbl_void*)(ls.kbase + (voff + kswz[k])),
-                                       (lds_void*)(smem + OFF_K + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB), 16, 0, 0);
-      if (lpos == 0) rowinfo[ms * BN + r_k[k]] = e < ls.nblk ? prow : -1;
+      for (int k = 0; k < RI; ++k) {
+        const int e = (g0 + (k * NW + wave) * RPI) >> ls.lg_th;                 // scalar
+        plan_jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];   // same address in every lane
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < RI; ++k) {
+        const int e = (g0 + r_k[k]) >> ls.lg_th;
+        plan_jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
+      }
     }
-    vbase_keep = ls.vbase;
-    if (__any(irregular)) special[ms] = t + 1;
-    if (tid == 0) tilebias[ms] = (float)(ls.h - 1);
+  };
+  auto plan_part = [&](int k) __attribute__((always_inline)) {
+    if (ls.lg_th >= LG_RPI) {
+      const int g = (ld_tl << 6) + (k * NW + wave) * RPI;        // first row of this load in the level's token stream
+      const int jj = __builtin_amdgcn_readfirstlane(plan_jj[k]);
+      const int prow0 = (jj << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
+      if (prow0 + RPI - 1 <= ls.rowmax) {
+        planK[k] = (uint32_t)prow0 * (uint32_t)ROWB + lane_rowoff;
+      } else {                                                   // ragged end of the unpadded level-1 array
+        const int prow = prow0 + lrow;
+        planK[k] = (uint32_t)(prow < ls.rowmax ? prow : ls.rowmax) * (uint32_t)ROWB;
+      }
+    } else {
+      const int g = (ld_tl << 6) + r_k[k];                       // position in the level's token stream
+      const int prow = (plan_jj[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));   // row in the level-h array
+      planK[k] = (uint32_t)(prow < ls.rowmax ? prow : ls.rowmax) * (uint32_t)ROWB;
+    }
+  };
+  auto plan_end = [&](int tp) __attribute__((always_inline)) {
+    planK_kbase = ls.kbase;
+    planK_vbase = ls.vbase;
+    const uint32_t sh = (uint32_t)(tp & 7);
+    spec_ring = (spec_ring & ~(1u << sh)) | ((__any(plan_irregular) ? 1u : 0u) << sh);
+    lvl_ring = (lvl_ring & ~(15u << (4 * sh))) | ((uint32_t)(ls.h - 1) << (4 * sh));
     ++ld_tl;
     if (ld_tl >= ls.ntl) {
       ld_tl = 0;
       do { enter_level(ls.h + 1, ls.lvl_start + ls.nblk); } while (ls.h <= a.H && ls.ntl == 0);
     }
   };
-  // V rows of the tile whose K was issued last -> V buffer t & 1
-  auto issue_v = [&](int t) __attribute__((always_inline)) {
+  auto fire_k = [&](int t) __attribute__((always_inline)) {      // K rows of tile t -> K buffer t & 1
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planK_kbase, 0, -1, RSRC_FLAGS);
 #pragma unroll
     for (int k = 0; k < RI; ++k)
-      __builtin_amdgcn_global_load_lds((gbl_void*)(vbase_keep + (voff_keep[k] + vswz[k])),
-                                       (lds_void*)(smem + OFF_V + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + OFF_K + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
+                                               16, (int)(planK[k] + kswz[k]), 0, 0, 0);
+  };
+  auto fire_v = [&](int t) __attribute__((always_inline)) {      // V rows of tile t -> V buffer t & 1
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planV_vbase, 0, -1, RSRC_FLAGS);
+#pragma unroll
+    for (int k = 0; k < RI; ++k)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + OFF_V + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
+                                               16, (int)(planV[k] + vswz[k]), 0, 0, 0);
+  };
+  auto k_plan_to_v = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < RI; ++k) planV[k] = planK[k];
+    planV_vbase = planK_vbase;
   };
 
-  if (tid < 4) special[tid] = 0;
-
   // ---- query fragments (B operand of S^T = K Q^T): lane holds one row, 8 channels per k-step
-  bf16x8 qf[QB][D / 16];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const bf16_t* qp = Q + (qhead * a.N + qrow[qb]) * D + hf * 8;
+  bf16x8 qf[D / 16];
+  {
+    const bf16_t* qp = Q + (qhead * a.N + qrow) * D + hf * 8;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (qrow[qb] < row_end) v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
-      qf[qb][ks] = __builtin_bit_cast(bf16x8, v);
+      if (qrow < row_end) v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+      qf[ks] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
-  f32x16 oacc[QB][D / 32];
-  float m_run[QB], l_run[QB];
+  f32x16 oacc[D / 32];
+  float m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+  for (int md = 0; md < D / 32; ++md)
 #pragma unroll
-    for (int md = 0; md < D / 32; ++md)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[qb][md][v] = 0.f;
-  }
+    for (int v = 0; v < 16; ++v) oacc[md][v] = 0.f;
 
   // ---- per-lane LDS read addresses (bytes, buffer 0; XOR with TILEB selects buffer 1)
   // K operand: row mb*32 + l32, chunk (2 ks + hf) ^ swizzle(row) = chunk(ks = 0) ^ 2 ks
@@ -249,218 +287,276 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     for (int md = 0; md < D / 32; ++md)
       vaddr[md] = (uint32_t)(OFF_V + v_row * ROWB + (((md * 4 + v_dsel * 2 + (v_q >> 1)) ^ fv_rd) << 4) + (v_q & 1) * 8);
   }
-
-  // S^T = K Q^T for tile t (K buffer t & 1): two 32-row halves of the 64 key columns; every K
-  // fragment feeds the MFMAs of all QB row groups.  Fragments are requested KB k-steps ahead.
-  auto qk_tile = [&](f32x16 (&sc)[QB][2], int t) __attribute__((always_inline)) {
-    const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
-    constexpr int KB = 4;                       // k-steps per batch
-    constexpr int NB = 2 * (D / 16) / KB;       // batches: (mb, ks-group)
-    bf16x8 kf[2][KB];
-    auto read_k = [&](int bi, int u) __attribute__((always_inline)) {
-      const int mb = bi / (NB / 2), ks = (bi % (NB / 2)) * KB + u;
-      return *reinterpret_cast<const bf16x8*>(smem + (kaddr0 ^ flip ^ (uint32_t)(ks << 5)) + mb * 32 * ROWB);
-    };
-#pragma unroll
-    for (int u = 0; u < KB; ++u) kf[0][u] = read_k(0, u);
-#pragma unroll
-    for (int bi = 0; bi < NB; ++bi) {
-      if (bi + 1 < NB) {
-#pragma unroll
-        for (int u = 0; u < KB; ++u) kf[(bi + 1) & 1][u] = read_k(bi + 1, u);
-      }
-      const int mb = bi / (NB / 2);
-#pragma unroll
-      for (int u = 0; u < KB; ++u) {
-        const int ks = (bi % (NB / 2)) * KB + u;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          if (ks == 0) {
-            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            sc[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[qb][ks], zero, 0, 0, 0);
-          } else {
-            sc[qb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[bi & 1][u], qf[qb][ks], sc[qb][mb], 0, 0, 0);
-          }
-        }
-      }
-    }
-    // issue order: KB LDS reads ahead, then one read per QB MFMAs
-    __builtin_amdgcn_sched_group_barrier(0x100, KB, 0);
-#pragma unroll
-    for (int i = 0; i < 2 * (D / 16) - KB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, KB * QB, 0);
+  // MFMA number j of the first product: key half j & 1, k-step j >> 1 (neighbours in issue order are
+  // independent); of the second product: channel block j % (D/32), k-step j / (D/32)
+  auto read_k = [&](int j, uint32_t flip) __attribute__((always_inline)) {
+    const int mb = j & 1, ks = j >> 1;
+    return *reinterpret_cast<const bf16x8*>(smem + (kaddr0 ^ flip ^ (uint32_t)(ks << 5)) + mb * 32 * ROWB);
   };
-
-  // online softmax (log2 domain) of one 32-row group of tile t -> bfloat16 P^T fragments.  register v
-  // of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
-  auto softmax_tile = [&](f32x16 (&sc)[2], bf16x8 (&pf)[4], f32x16 (&oa)[D / 32], float& mr, float& lr, int myrow,
-                          int t) __attribute__((always_inline)) {
-    const int ms = t & 3;
-    const float tbias = tilebias[ms];
-    const bool slow = special[ms] == t + 1;
-    float tmax = -INFINITY;
-    if (slow) {
-      const int hm1 = (int)tbias;
-      const int span = 1 << hm1;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int col = mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-          const int pr = rowinfo[ms * BN + col];
-          const int first = pr << hm1;
-          int c = a.N - first;
-          c = c < 0 ? 0 : (c > span ? span : c);
-          if (pr < 0) c = 0;
-          float x = sc[mb][v] * a.scale_log2 + __log2f((float)c);   // log2(0) = -inf masks the key
-          if (a.causal && first + c - 1 > myrow) x = -INFINITY;
-          if (c == 0) x = -INFINITY;
-          sc[mb][v] = x;
-          tmax = fmaxf(tmax, x);
-        }
-    } else {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, sc[mb][v]);
-      tmax = tmax * a.scale_log2 + tbias;
-    }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    if (__any(tmax - mr > LAZY_RESCALE)) {
-      const float m_new = fmaxf(mr, tmax);
-      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(mr - m_new);
-      lr *= alpha;
-#pragma unroll
-      for (int md = 0; md < D / 32; ++md)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oa[md][v] *= alpha;
-      mr = m_new;
-    }
-    const float m_use = mr == -INFINITY ? 0.f : mr;
-    if (slow) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(sc[mb][v] - m_use);
-          lr += p;
-          pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
-        }
-    } else {
-      const float shift = tbias - m_use;
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
-          lr += p;
-          pf[2 * mb + (v >> 3)][v & 7] = (__bf16)p;
-        }
-    }
+  auto read_vt = [&](int j, uint32_t flip) __attribute__((always_inline)) {
+    const int md = j % (D / 32), ks = j / (D / 32);
+    const unsigned char* vp = smem + (vaddr[md] ^ flip) + ks * 16 * ROWB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
+    return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x2 ones2;
+  ones2[0] = (__bf16)1.0f;
+  ones2[1] = (__bf16)1.0f;
 
-  // O^T += V^T P^T for tile t (V buffer t & 1): contraction index (hf, e) of k-step ks is key column
-  // ks*16 + (e/4)*8 + hf*4 + e%4, matching the P^T registers.  One channel block at a time, the V^T
-  // fragments of the next block requested while the current one multiplies; every fragment feeds the
-  // MFMAs of all QB row groups.
-  auto pv_tile = [&](const bf16x8 (&pf)[QB][4], int t) __attribute__((always_inline)) {
-    const uint32_t flip = (t & 1) ? (uint32_t)TILEB : 0u;
-    auto read_vt = [&](int md, int ks) __attribute__((always_inline)) {
-      const unsigned char* vp = smem + (vaddr[md] ^ flip) + ks * 16 * ROWB;
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
-      return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-    bf16x8 vf[2][4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) vf[0][ks] = read_vt(0, ks);
-#pragma unroll
-    for (int md = 0; md < D / 32; ++md) {
-      if (md + 1 < D / 32) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) vf[(md + 1) & 1][ks] = read_vt(md + 1, ks);
-      }
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          oacc[qb][md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[md & 1][ks], pf[qb][ks], oacc[qb][md], 0, 0, 0);
+  // Irregular tile (end of a level, ragged tail, causal edge): rewrite the raw scores so that the
+  // regular path, which adds the tile's constant (h-1) to scale*s, produces scale*s + log2(count) for
+  // a pooled key that covers `count` valid visible tokens and -inf for a key that must not be seen.
+  // Rare, so the tile's place in the list is found again from the level counts.
+  // register v of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
+  auto fixup_special = [&](f32x16 (&sc)[2], int t) __attribute__((always_inline)) {
+    int h = 1, start = 0, tl = t, nb = 0, lg_th = a.lg_bk;
+    for (;; ++h) {
+      nb = my_cnt[h - 1];
+      lg_th = a.lg_bk - (h - 1);
+      const int ntl = ((nb << lg_th) + BN - 1) >> 6;
+      if (tl < ntl || h == a.H) break;
+      tl -= ntl;
+      start += nb;
     }
-    // issue order: the 8 transposing reads of one channel block ahead, then two reads per QB MFMAs
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-    for (int i = 0; i < 4 * (D / 32 - 1); ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 4 * QB, 0);
-  };
-
-  // One step per tile:  wait + barrier | issue V(t+1), K(t+2) | QK(t+1) | softmax(t) | PV(t)
-  auto step = [&](f32x16 (&sc)[QB][2], f32x16 (&sn)[QB][2], int t) __attribute__((always_inline)) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's K(t+1), V(t) have landed
-    __syncthreads();                          // ... and everyone else's; buffers of K(t), V(t-1) are free
-    if (t + 1 < total_tiles) issue_v(t + 1);
-    if (t + 2 < total_tiles) issue_k(t + 2);
-    if (t + 1 < total_tiles) qk_tile(sn, t + 1);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 pf[QB][4];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) softmax_tile(sc[qb], pf[qb], oacc[qb], m_run[qb], l_run[qb], qrow[qb], t);
-    __builtin_amdgcn_sched_barrier(0);
-    pv_tile(pf, t);
-  };
-
-  f32x16 sA[QB][2], sB[QB][2];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
+    const int hm1 = h - 1;
+    const float tbias = (float)hm1;
+    const int span = 1 << hm1;
+    const float inv_scale = 1.f / a.scale_log2;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { sA[qb][mb][v] = 0.f; sB[qb][mb][v] = 0.f; }
-  __syncthreads();                           // block list and special[] are in LDS
+      for (int v = 0; v < 16; ++v) {
+        const int col = mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+        const int g = (tl << 6) + col, e = g >> lg_th;
+        const int jj = (int)list[start + (e < nb ? e : nb - 1)];
+        const int pr = (jj << lg_th) | (g & ((1 << lg_th) - 1));     // row in the level-h array
+        const int first = pr << hm1;
+        int c = a.N - first;
+        c = c < 0 ? 0 : (c > span ? span : c);
+        if (e >= nb) c = 0;
+        float x = sc[mb][v] + (__log2f((float)c) - tbias) * inv_scale;
+        if (a.causal && first + c - 1 > qrow) x = -INFINITY;
+        if (c == 0) x = -INFINITY;
+        sc[mb][v] = x;
+      }
+  };
+
+  // The two lanes that share a query row sit 32 apart.  The swap leaves the row's low-half value in
+  // both halves of one result register and the high-half value in both halves of the other.
+  auto both_halves = [&](float x, float& p, float& q) __attribute__((always_inline)) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    uint32_t u2 = u;
+    asm volatile("" : "+v"(u2));   // two distinct operands: with one value twice the optimiser treats both results as equal
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u2, false, false);
+    uint32_t r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    p = __builtin_bit_cast(float, r0);
+    q = __builtin_bit_cast(float, r1);
+  };
+
+  // Running maximum after seeing tile t whose raw-score maximum (per lane) is `rawmax`; returns the
+  // constant of the exponent, p = 2^(scale*s + shift).  The maximum only advances when it grows by
+  // more than LAZY_RESCALE, so the accumulator rescale is off the common path.
+  auto advance_max = [&](float rawmax, int t) __attribute__((always_inline)) -> float {
+    const float tbias = (float)((lvl_ring >> (4 * (t & 7))) & 15u);
+    float tmax = rawmax * a.scale_log2 + tbias;
+    {
+      float p, q;
+      both_halves(tmax, p, q);
+      tmax = fmaxf(p, q);
+    }
+    if (__any(tmax - m_run > LAZY_RESCALE)) {
+      const float m_new = fmaxf(m_run, tmax);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int md = 0; md < D / 32; ++md)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[md][v] *= alpha;
+      m_run = m_new;
+    }
+    return tbias - (m_run == -INFINITY ? 0.f : m_run);
+  };
+
+  // EPC probabilities of the current tile: p = 2^(scale*s + shift) -> bfloat16 P^T registers, row sum
+  // taken over the rounded values (the ones the second product multiplies)
+  auto exp_chunk = [&](const f32x16 (&sc)[2], bf16x8 (&pf)[4], float shift, int j) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < EPC; u += 2) {
+      const int e = j * EPC + u, mb = e >> 4, v = e & 15;
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v + 1], a.scale_log2, shift));
+      bf16x2 pk;
+      pk[0] = (__bf16)p0;
+      pk[1] = (__bf16)p1;
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, l_run, false);
+      {  // keep the arithmetic in this slice: pure values are otherwise free to sink to their first use
+        uint32_t bits = __builtin_bit_cast(uint32_t, pk);
+        asm volatile("" : "+v"(bits), "+v"(l_run));
+        pk = __builtin_bit_cast(bf16x2, bits);
+      }
+      pf[2 * mb + (v >> 3)][v & 7] = pk[0];
+      pf[2 * mb + (v >> 3)][(v & 7) + 1] = pk[1];
+    }
+  };
+
+  // One step per tile t (MORE: a tile t+1 exists):
+  //   wait + barrier | fire V(t+1), K(t+2)
+  //   first product of tile t+1, each MFMA followed by a slice of the exponentials of tile t
+  //   second product of tile t, each MFMA followed by a slice of the plan of tile t+3 and of the
+  //   maximum of tile t+1
+  // The order inside the two phases is fixed by hand (scheduling fences between the slices): the
+  // matrix pipe executes one MFMA while the vector unit works through the slice behind it.
+  float shift_cur = 0.f;                      // exponent constant of the tile whose scores are current
+  auto step = [&](auto more_tag, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
+    constexpr bool MORE = decltype(more_tag)::value;
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's K(t+1), V(t) have landed
+    __syncthreads();                          // ... and everyone else's; buffers of K(t), V(t-1) are free
+    if (MORE) fire_v(t + 1);
+    const bool k2 = MORE && t + 2 < total_tiles;
+    if (k2) { fire_k(t + 2); k_plan_to_v(); }
+    const bool k3 = MORE && t + 3 < total_tiles;
+    const uint32_t flip_n = ((t + 1) & 1) ? (uint32_t)TILEB : 0u;
+    const uint32_t flip_c = (t & 1) ? (uint32_t)TILEB : 0u;
+    bf16x8 pf[4];
+    bf16x8 fr[4];                             // rolling operand fragments, requested PF MFMAs ahead
+    constexpr int PF = 3;
+    __builtin_amdgcn_sched_barrier(0);
+    if (MORE) {
+#pragma unroll
+      for (int j = 0; j < PF; ++j) fr[j] = read_k(j, flip_n);
+    }
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+      if (MORE) {
+        if (j + PF < NA) fr[(j + PF) & 3] = read_k(j + PF, flip_n);
+        const int mb = j & 1, ks = j >> 1;
+        sn[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], qf[ks], ks == 0 ? zero16 : sn[mb], 0, 0, 0);
+      }
+      exp_chunk(sc, pf, shift_cur, j);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (MORE) {
+      if ((spec_ring >> ((t + 1) & 7)) & 1u) fixup_special(sn, t + 1);
+      if (k3) plan_begin();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < PF; ++j) fr[j] = read_vt(j, flip_c);
+    float rawmax = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      if (j + PF < NB) fr[(j + PF) & 3] = read_vt(j + PF, flip_c);
+      const int md = j % (D / 32), ks = j / (D / 32);
+      oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], pf[ks], oacc[md], 0, 0, 0);
+      if (MORE) {
+        if (k3) {
+#pragma unroll
+          for (int k = j; k < RI; k += NB) plan_part(k);
+        }
+#pragma unroll
+        for (int u = 0; u < MPC; ++u) {
+          const int e = (j * MPC + u) * 2, mb = e >> 4, v = e & 15;
+          rawmax = fmaxf(rawmax, fmaxf(sn[mb][v], sn[mb][v + 1]));
+        }
+        asm volatile("" : "+v"(rawmax));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (MORE) {
+      if (k3) plan_end(t + 3);
+      shift_cur = advance_max(rawmax, t + 1);
+    }
+  };
+
+  f32x16 sA[2], sB[2];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sA[mb][v] = 0.f; sB[mb][v] = 0.f; }
+  __syncthreads();                           // block list is in LDS
   if (total_tiles > 0) {
-    issue_k(0);
+    // prologue: plans of tiles 0..2, loads of K(0), V(0), K(1), scores and maximum of tile 0
+    plan_begin();
+#pragma unroll
+    for (int k = 0; k < RI; ++k) plan_part(k);
+    plan_end(0);
+    fire_k(0);
+    k_plan_to_v();
+    if (total_tiles > 1) {
+      plan_begin();
+#pragma unroll
+      for (int k = 0; k < RI; ++k) plan_part(k);
+      plan_end(1);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    issue_v(0);
-    if (total_tiles > 1) issue_k(1);
-    qk_tile(sA, 0);
+    fire_v(0);
+    if (total_tiles > 1) { fire_k(1); k_plan_to_v(); }
+    if (total_tiles > 2) {
+      plan_begin();
+#pragma unroll
+      for (int k = 0; k < RI; ++k) plan_part(k);
+      plan_end(2);
+    }
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+      const int mb = j & 1, ks = j >> 1;
+      sA[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(j, 0u), qf[ks], ks == 0 ? zero16 : sA[mb], 0, 0, 0);
+    }
+    if (spec_ring & 1u) fixup_special(sA, 0);
+    float rawmax = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) rawmax = fmaxf(rawmax, sA[mb][v]);
+    shift_cur = advance_max(rawmax, 0);
   }
-  for (int t = 0; t < total_tiles; t += 2) {
-    step(sA, sB, t);
-    if (t + 1 < total_tiles) step(sB, sA, t + 1);
+  {
+    const std::true_type more;
+    const std::false_type last;
+    int t = 0;
+    for (; t + 2 < total_tiles; t += 2) {
+      step(more, sA, sB, t);
+      step(more, sB, sA, t + 1);
+    }
+    if (t + 1 < total_tiles) {
+      step(more, sA, sB, t);
+      step(last, sB, sA, t + 1);
+    } else if (t < total_tiles) {
+      step(last, sA, sB, t);
+    }
   }
 
   // ---- epilogue: O = o / l ; lane (row, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-    if (qrow[qb] < row_end) {
+  {
+    float l_lo, l_hi;
+    both_halves(l_run, l_lo, l_hi);
+    const float l_tot = l_lo + l_hi;
+    if (qrow < row_end) {
       const float inv = 1.f / l_tot;
-      bf16_t* op = O + (qhead * a.N + qrow[qb]) * D;
+      bf16_t* op = O + (qhead * a.N + qrow) * D;
 #pragma unroll
       for (int md = 0; md < D / 32; ++md)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           bf16x4 w;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[qb][md][4 * g + e] * inv);
+          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[md][4 * g + e] * inv);
           *reinterpret_cast<bf16x4*>(op + md * 32 + g * 8 + hf * 4) = w;
         }
-      if (lse && hf == 0) lse[qhead * a.N + qrow[qb]] = (m_run[qb] + __log2f(l_tot)) * 0.69314718055994531f;
+      if (lse && hf == 0) lse[qhead * a.N + qrow] = (m_run + __log2f(l_tot)) * 0.69314718055994531f;
     }
   }
 }
 
 size_t attn_mfma_smem_bytes(int d, int nk) {
-  return 4 * (size_t)BN * d * sizeof(bf16_t) + 4 * BN * sizeof(int) + 32 + (((size_t)nk * 2 + 15) & ~(size_t)15);
+  return 4 * (size_t)BN * d * sizeof(bf16_t) + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
-template <int D, int NW, int QB>
+template <int D, int NW>
 static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                                 const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                                 hipStream_t s) {
@@ -469,13 +565,13 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.H = pl.H; a.causal = pl.causal;
   a.lg_bk = 0;
   while ((1 << a.lg_bk) < pl.bk) ++a.lg_bk;
-  constexpr int ROWS = NW * QB * 32;
+  constexpr int ROWS = NW * 32;
   a.slices = (pl.bq + ROWS - 1) / ROWS;
   a.items = pl.B * pl.Hq * pl.nq * a.slices;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
   const size_t smem = attn_mfma_smem_bytes(D, pl.nk);
-  auto kern = attn_mfma_kernel<D, NW, QB>;
+  auto kern = attn_mfma_kernel<D, NW>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)smem);
   if (e != hipSuccess) return e;
@@ -491,15 +587,15 @@ hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const 
   const int rows = pl.bq < 128 ? pl.bq : 128;   // rows per workgroup
   if (pl.d == 128) {
     switch (rows) {
-      case 32: return launch_mfma_t<128, 1, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_t<128, 2, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_t<128, 4, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_t<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_t<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_t<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   } else if (pl.d == 64) {
     switch (rows) {
-      case 32: return launch_mfma_t<64, 1, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_t<64, 2, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_t<64, 4, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_t<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_t<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_t<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   }
   return hipErrorInvalidValue;
