@@ -47,6 +47,8 @@ constexpr int RSRC_FLAGS = 0x00020000;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 // Scalar (wave-uniform) description of the level the loader is walking.
 struct LevelState {
@@ -56,13 +58,14 @@ struct LevelState {
   int ntl;          // tiles of this level
   int lvl_start;    // position of the level's first block in the row's list
   int lim;          // pooled rows >= lim are partly invalid (ragged tail) or not visible to every row
-  int rowmax;       // clamp for the source row (level 1 is not padded to whole blocks)
+  uint32_t nrec;    // bytes of this head's level array (level 1 is not padded to whole blocks)
   const char* kbase;
   const char* vbase;
 };
 
-// D: head dimension; NW: wavefronts per workgroup (each owns 32 query rows)
-template <int D, int NW>
+// D: head dimension; NW: wavefronts per workgroup (each owns 32 query rows); SC: every level's pooled
+// block holds at least as many rows as one load instruction covers
+template <int D, int NW, bool SC>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                       const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
@@ -79,13 +82,12 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   constexpr int TILEB = BN * ROWB;           // bytes per tile (a power of two)
   constexpr int NA = 2 * (D / 16);           // MFMAs of S^T = K Q^T per tile
   constexpr int NB = 4 * (D / 32);           // MFMAs of O^T += V^T P^T per tile
-  constexpr int EPC = 32 / NA;               // softmax elements handled next to one MFMA of the first product
   constexpr int MPC = 16 / NB;               // 3-input maxima handled next to one MFMA of the second product
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-  static_assert(EPC * NA == 32 && MPC * NB == 16 && EPC % 2 == 0, "chunking of the softmax work");
-  // LDS map: K[2] | V[2] | block list
+  static_assert(MPC * NB == 16, "chunking of the softmax work");
+  // LDS map: K[2] | V[2] | per-wavefront table for irregular tiles | block list
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_LIST = 4 * TILEB;
+  constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_FIX = 4 * TILEB, OFF_LIST = OFF_FIX + NW * 512;
   uint16_t* list = reinterpret_cast<uint16_t*>(smem + OFF_LIST);    // kept block ids, level-major
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -123,12 +125,19 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     total_tiles += ((nb << lg_th) + BN - 1) >> 6;
   }
   for (int x = tid; x < total_blocks; x += NT) list[x] = my_idx[x];
+  {  // tile buffers start as zeros: a lane whose source row is out of range leaves its LDS slot alone
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int x = tid * 16; x < 4 * TILEB; x += NT * 16) *reinterpret_cast<u32x4*>(smem + x) = z;
+  }
 
   LevelState ls;
   auto enter_level = [&](int h, int lvl_start) __attribute__((always_inline)) {   // scalar work, once per level
     ls.h = h;
     ls.lvl_start = lvl_start;
-    if (h > a.H) { ls.nblk = 0; ls.ntl = 0; return; }
+    if (h > a.H) {     // past the last tile: null tiles, whose loads are all out of range and fetch nothing
+      ls.nblk = 1; ls.ntl = 0x7fffffff; ls.lg_th = a.lg_bk; ls.lim = 0x7fffffff; ls.nrec = 0; ls.lvl_start = 0;
+      return;
+    }
     ls.lg_th = a.lg_bk - (h - 1);
     ls.nblk = my_cnt[h - 1];
     ls.ntl = ((ls.nblk << ls.lg_th) + BN - 1) >> 6;
@@ -138,8 +147,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       lim = vis < lim ? vis : lim;
     }
     ls.lim = lim;
-    ls.rowmax = h == 1 ? a.N - 1 : 0x7fffffff;
     const int64_t rows_h = (int64_t)a.nk << ls.lg_th;
+    ls.nrec = (uint32_t)(h == 1 ? (int64_t)a.N : rows_h) * (uint32_t)(D * 2);
     if (h == 1) {
       ls.kbase = reinterpret_cast<const char*>(K + khead * (int64_t)a.N * D);
       ls.vbase = reinterpret_cast<const char*>(V + khead * (int64_t)a.N * D);
@@ -155,14 +164,16 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // ---- per-lane constants of the loader
   const int lrow = lane / CPR;               // row within one load instruction
   const int lpos = lane % CPR;               // 16-byte slot within the LDS row
-  int r_k[RI];
-  uint32_t kswz[RI], vswz[RI];
+  // byte offset of this lane inside the rows of load k, with the bank swizzle of its LDS row: the
+  // 16-byte chunks of a row are XOR-ed with a row-dependent value on the global-address side.  The
+  // swizzle repeats every KP loads.
+  constexpr int KP = 16 / (NW * RPI) > 1 ? 16 / (NW * RPI) : 1;
+  uint32_t klane[KP], vlane[KP];
 #pragma unroll
-  for (int k = 0; k < RI; ++k) {
+  for (int k = 0; k < KP; ++k) {
     const int r = (k * NW + wave) * RPI + lrow;
-    r_k[k] = r;
-    kswz[k] = (uint32_t)((lpos ^ ((r / RP256) % CPR)) << 4);              // spreads 16 rows over all banks
-    vswz[k] = (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);  // spreads 4 rows x 64 B
+    klane[k] = (uint32_t)(lrow * ROWB) + (uint32_t)((lpos ^ ((r / RP256) % CPR)) << 4);              // spreads 16 rows over all banks
+    vlane[k] = (uint32_t)(lrow * ROWB) + (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);  // spreads 4 rows x 64 B
   }
 
   // The loader works in two stages.  PLAN (arithmetic only, besides block ids read from the list in
@@ -171,26 +182,31 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // its level, and whether it is irregular (see fixup_special).  FIRE: the direct-to-LDS loads of a
   // planned tile.  Plans run ahead of the loads so that their arithmetic sits between the MFMAs of the
   // second product.
-  //   planK: offsets of the tile whose K rows go out next; planV: tile whose V rows go out next
-  uint32_t planK[RI], planV[RI];
-  const char *planK_kbase = nullptr, *planK_vbase = nullptr, *planV_vbase = nullptr;
+  // K rows of a tile are requested one and a half steps before the first product needs them, V rows
+  // one and a half steps before the second product does, so three plans are alive:
+  //   planK: tile whose K rows go out next; planV1: tile whose V rows go out next; planV2: the one after
+  uint32_t planK[RI], planV1[RI], planV2[RI];
+  const char *planK_kbase = nullptr, *planK_vbase = nullptr, *planV1_vbase = nullptr, *planV2_vbase = nullptr;
+  uint32_t planK_nrec = 0, planV1_nrec = 0, planV2_nrec = 0;
   int plan_jj[RI];
   bool plan_irregular = false;
   uint32_t lvl_ring = 0, spec_ring = 0;       // per tile mod 8: 4 bits of level - 1; 1 bit irregular
   constexpr int LG_RPI = RPI == 4 ? 2 : (RPI == 8 ? 3 : -1);
   static_assert(LG_RPI > 0, "rows per load instruction");
-  const uint32_t lane_rowoff = (uint32_t)(lrow * ROWB);
   // A level whose pooled blocks hold at least RPI rows: each load instruction stays inside one block,
   // so the block id and the row offset are wave-uniform and computed on the scalar unit.
-  auto plan_begin = [&]() __attribute__((always_inline)) {
+  // The plan of a tile is spread over a step: plan_read (block ids requested from the list in LDS)
+  // at its start, plan_resolve (ids to scalar registers, irregularity test) once the first product is
+  // out, plan_part (offsets; arithmetic only) between the MFMAs of the second product, plan_end.
+  int plan_jl = 0;                            // block id of tile row `lane`
+  int plan_js[RI];                            // wave-uniform block id of each load
+  auto plan_read = [&]() __attribute__((always_inline)) {
     const int g0 = ld_tl << 6;
-    {  // the whole tile, one row per lane: is any row past the kept blocks, the ragged tail or the causal limit?
-      const int g = g0 + lane, e = g >> ls.lg_th;
-      const int jl = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
-      const int prow = (jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
-      plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
+    {
+      const int e = (g0 + lane) >> ls.lg_th;
+      plan_jl = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
     }
-    if (ls.lg_th >= LG_RPI) {
+    if (SC) {
 #pragma unroll
       for (int k = 0; k < RI; ++k) {
         const int e = (g0 + (k * NW + wave) * RPI) >> ls.lg_th;                 // scalar
@@ -199,31 +215,37 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     } else {
 #pragma unroll
       for (int k = 0; k < RI; ++k) {
-        const int e = (g0 + r_k[k]) >> ls.lg_th;
+        const int e = (g0 + (k * NW + wave) * RPI + lrow) >> ls.lg_th;
         plan_jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
       }
     }
   };
+  auto plan_resolve = [&]() __attribute__((always_inline)) {
+    {  // the whole tile, one row per lane: is any row past the kept blocks, the ragged tail or the causal limit?
+      const int g = (ld_tl << 6) + lane, e = g >> ls.lg_th;
+      const int prow = (plan_jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
+      plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
+    }
+    if (SC) {
+#pragma unroll
+      for (int k = 0; k < RI; ++k) plan_js[k] = __builtin_amdgcn_readfirstlane(plan_jj[k]);
+    }
+  };
   auto plan_part = [&](int k) __attribute__((always_inline)) {
-    if (ls.lg_th >= LG_RPI) {
+    if (SC) {
       const int g = (ld_tl << 6) + (k * NW + wave) * RPI;        // first row of this load in the level's token stream
-      const int jj = __builtin_amdgcn_readfirstlane(plan_jj[k]);
-      const int prow0 = (jj << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
-      if (prow0 + RPI - 1 <= ls.rowmax) {
-        planK[k] = (uint32_t)prow0 * (uint32_t)ROWB + lane_rowoff;
-      } else {                                                   // ragged end of the unpadded level-1 array
-        const int prow = prow0 + lrow;
-        planK[k] = (uint32_t)(prow < ls.rowmax ? prow : ls.rowmax) * (uint32_t)ROWB;
-      }
+      const int prow0 = (plan_js[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
+      planK[k] = (uint32_t)prow0 * (uint32_t)ROWB;               // wave-uniform: stays in a scalar register
     } else {
-      const int g = (ld_tl << 6) + r_k[k];                       // position in the level's token stream
+      const int g = (ld_tl << 6) + (k * NW + wave) * RPI + lrow;   // position in the level's token stream
       const int prow = (plan_jj[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));   // row in the level-h array
-      planK[k] = (uint32_t)(prow < ls.rowmax ? prow : ls.rowmax) * (uint32_t)ROWB;
+      planK[k] = (uint32_t)(prow - lrow) * (uint32_t)ROWB;       // (the lane's own row offset is in klane / vlane)
     }
   };
   auto plan_end = [&](int tp) __attribute__((always_inline)) {
     planK_kbase = ls.kbase;
     planK_vbase = ls.vbase;
+    planK_nrec = ls.nrec;
     const uint32_t sh = (uint32_t)(tp & 7);
     spec_ring = (spec_ring & ~(1u << sh)) | ((__any(plan_irregular) ? 1u : 0u) << sh);
     lvl_ring = (lvl_ring & ~(15u << (4 * sh))) | ((uint32_t)(ls.h - 1) << (4 * sh));
@@ -234,23 +256,37 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
   };
   auto fire_k = [&](int t) __attribute__((always_inline)) {      // K rows of tile t -> K buffer t & 1
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planK_kbase, 0, -1, RSRC_FLAGS);
+    // rows past the end of the unpadded level-1 array are out of the descriptor's range: such lanes
+    // read nothing (the scores of those columns are masked, see fixup_special)
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planK_kbase, 0, (int)planK_nrec, RSRC_FLAGS);
 #pragma unroll
     for (int k = 0; k < RI; ++k)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + OFF_K + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
-                                               16, (int)(planK[k] + kswz[k]), 0, 0, 0);
+                                               16, (int)(planK[k] + klane[k % KP]), 0, 0, 0);
   };
   auto fire_v = [&](int t) __attribute__((always_inline)) {      // V rows of tile t -> V buffer t & 1
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planV_vbase, 0, -1, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)planV1_vbase, 0, (int)planV1_nrec, RSRC_FLAGS);
 #pragma unroll
     for (int k = 0; k < RI; ++k)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + OFF_V + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
-                                               16, (int)(planV[k] + vswz[k]), 0, 0, 0);
+                                               16, (int)(planV1[k] + vlane[k % KP]), 0, 0, 0);
   };
-  auto k_plan_to_v = [&]() __attribute__((always_inline)) {
+  auto rotate_plans = [&]() __attribute__((always_inline)) {     // after the K rows of planK have gone out
 #pragma unroll
-    for (int k = 0; k < RI; ++k) planV[k] = planK[k];
-    planV_vbase = planK_vbase;
+    for (int k = 0; k < RI; ++k) { planV1[k] = planV2[k]; planV2[k] = planK[k]; }
+    planV1_vbase = planV2_vbase;
+    planV2_vbase = planK_vbase;
+    planV1_nrec = planV2_nrec;
+    planV2_nrec = planK_nrec;
+  };
+  // Workgroup barrier without the compiler's memory fence (which would wait for every direct-to-LDS
+  // load in flight): the loads a phase depends on are waited for explicitly, by count.
+  auto wg_barrier = [&]() __attribute__((always_inline)) { asm volatile("s_barrier" ::: "memory"); };
+  // wait until at most `groups` of this wavefront's tile-load groups (RI loads each) are still in flight
+  auto wait_loads = [&](bool two_behind) __attribute__((always_inline)) {
+    constexpr int N2 = 2 * RI;
+    if (two_behind) __builtin_amdgcn_s_waitcnt((N2 & 15) | ((N2 >> 4) << 14) | 0x0F70);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
   // ---- query fragments (B operand of S^T = K Q^T): lane holds one row, 8 channels per k-step
@@ -267,6 +303,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 
   f32x16 oacc[D / 32];
   float m_run = -INFINITY, l_run = 0.f;
+  float l_part = 0.f;                         // second partial row sum; folded into l_run at the end
 #pragma unroll
   for (int md = 0; md < D / 32; ++md)
 #pragma unroll
@@ -289,27 +326,45 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   }
   // MFMA number j of the first product: key half j & 1, k-step j >> 1 (neighbours in issue order are
   // independent); of the second product: channel block j % (D/32), k-step j / (D/32)
-  auto read_k = [&](int j, uint32_t flip) __attribute__((always_inline)) {
+  auto read_k = [&](int j, uint32_t flip) __attribute__((always_inline)) {   // compiler-managed (prologue only)
     const int mb = j & 1, ks = j >> 1;
     return *reinterpret_cast<const bf16x8*>(smem + (kaddr0 ^ flip ^ (uint32_t)(ks << 5)) + mb * 32 * ROWB);
   };
-  auto read_vt = [&](int j, uint32_t flip) __attribute__((always_inline)) {
+  // In the steady state every read of a K / V tile is written as assembly with its own counter
+  // waits.  Issued as ordinary loads (or through the transposing-read builtin) they are taken to
+  // possibly alias the direct-to-LDS loads still in flight into the OTHER buffer, and the compiler
+  // makes each phase wait for tiles that were requested for later steps.  An LDS counter wait that
+  // only counts the reads of the sequence issued after the wanted one is safe: LDS operations
+  // complete in order, and other LDS work in between only makes the wait stricter.
+  uint32_t kaddr[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) kaddr[ks] = kaddr0 ^ (uint32_t)(ks << 5);
+  auto read_k_asm = [&](bf16x8& dst, int j, int flip) __attribute__((always_inline)) {
+    const int mb = j & 1, ks = j >> 1;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(kaddr[ks]), "n"(flip + mb * 32 * ROWB));
+  };
+  auto take_k = [&](bf16x8& frag, int later) __attribute__((always_inline)) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(later));
+  };
+  auto read_vt = [&](s16x4& lo, s16x4& hi, int j, int flip) __attribute__((always_inline)) {
     const int md = j % (D / 32), ks = j / (D / 32);
-    const unsigned char* vp = smem + (vaddr[md] ^ flip) + ks * 16 * ROWB;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)vp);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vp + 8 * ROWB));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(vaddr[md]), "n"(flip + ks * 16 * ROWB));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(vaddr[md]), "n"(flip + ks * 16 * ROWB + 8 * ROWB));
+  };
+  // fragment whose reads were followed by `later` more reads of the sequence
+  auto take_vt = [&](s16x4& lo, s16x4& hi, int later) __attribute__((always_inline)) -> bf16x8 {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(later));
     return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  bf16x2 ones2;
-  ones2[0] = (__bf16)1.0f;
-  ones2[1] = (__bf16)1.0f;
 
   // Irregular tile (end of a level, ragged tail, causal edge): rewrite the raw scores so that the
   // regular path, which adds the tile's constant (h-1) to scale*s, produces scale*s + log2(count) for
   // a pooled key that covers `count` valid visible tokens and -inf for a key that must not be seen.
-  // Rare, so the tile's place in the list is found again from the level counts.
-  // register v of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile
+  // Rare, so the tile's place in the list is found again from the level counts.  Each lane works out
+  // one of the 64 key columns (additive term, last covered token) into a table private to the
+  // wavefront; then every lane reads the terms of the columns its registers hold:
+  // register v of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile.
   auto fixup_special = [&](f32x16 (&sc)[2], int t) __attribute__((always_inline)) {
     int h = 1, start = 0, tl = t, nb = 0, lg_th = a.lg_bk;
     for (;; ++h) {
@@ -321,25 +376,33 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       start += nb;
     }
     const int hm1 = h - 1;
-    const float tbias = (float)hm1;
     const int span = 1 << hm1;
-    const float inv_scale = 1.f / a.scale_log2;
+    float* term = reinterpret_cast<float*>(smem + OFF_FIX + wave * 512);
+    int* last = reinterpret_cast<int*>(smem + OFF_FIX + wave * 512 + 256);
+    {
+      const int g = (tl << 6) + lane, e = g >> lg_th;
+      const int jj = (int)list[start + (e < nb ? e : nb - 1)];
+      const int pr = (jj << lg_th) | (g & ((1 << lg_th) - 1));       // row in the level-h array
+      const int first = pr << hm1;
+      int c = a.N - first;
+      c = c < 0 ? 0 : (c > span ? span : c);
+      if (e >= nb) c = 0;
+      term[lane] = c == 0 ? -INFINITY : (__log2f((float)c) - (float)hm1) / a.scale_log2;
+      last[lane] = first + c - 1;
+    }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int col = mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-        const int g = (tl << 6) + col, e = g >> lg_th;
-        const int jj = (int)list[start + (e < nb ? e : nb - 1)];
-        const int pr = (jj << lg_th) | (g & ((1 << lg_th) - 1));     // row in the level-h array
-        const int first = pr << hm1;
-        int c = a.N - first;
-        c = c < 0 ? 0 : (c > span ? span : c);
-        if (e >= nb) c = 0;
-        float x = sc[mb][v] + (__log2f((float)c) - tbias) * inv_scale;
-        if (a.causal && first + c - 1 > qrow) x = -INFINITY;
-        if (c == 0) x = -INFINITY;
-        sc[mb][v] = x;
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = mb * 32 + g4 * 8 + hf * 4;
+        const f32x4 tm = *reinterpret_cast<const f32x4*>(term + col);
+        const i32x4 la = *reinterpret_cast<const i32x4*>(last + col);
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          float x = sc[mb][g4 * 4 + e4] + tm[e4];
+          if (a.causal && la[e4] > qrow) x = -INFINITY;
+          sc[mb][g4 * 4 + e4] = x;
+        }
       }
   };
 
@@ -371,6 +434,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       const float m_new = fmaxf(m_run, tmax);
       const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
       l_run *= alpha;
+      l_part *= alpha;
 #pragma unroll
       for (int md = 0; md < D / 32; ++md)
 #pragma unroll
@@ -380,27 +444,31 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     return tbias - (m_run == -INFINITY ? 0.f : m_run);
   };
 
-  // EPC probabilities of the current tile: p = 2^(scale*s + shift) -> bfloat16 P^T registers, row sum
-  // taken over the rounded values (the ones the second product multiplies)
-  auto exp_chunk = [&](const f32x16 (&sc)[2], bf16x8 (&pf)[4], float shift, int j) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < EPC; u += 2) {
-      const int e = j * EPC + u, mb = e >> 4, v = e & 15;
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v + 1], a.scale_log2, shift));
-      bf16x2 pk;
-      pk[0] = (__bf16)p0;
-      pk[1] = (__bf16)p1;
-      l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, l_run, false);
-      {  // keep the arithmetic in this slice: pure values are otherwise free to sink to their first use
-        uint32_t bits = __builtin_bit_cast(uint32_t, pk);
-        asm volatile("" : "+v"(bits), "+v"(l_run));
-        pk = __builtin_bit_cast(bf16x2, bits);
-      }
-      pf[2 * mb + (v >> 3)][v & 7] = pk[0];
-      pf[2 * mb + (v >> 3)][(v & 7) + 1] = pk[1];
+  // One pair of probabilities of the current tile: p = 2^(scale*s + shift) -> bfloat16 P^T registers
+  // and the two partial row sums.  Pair q holds tile columns of registers 2q, 2q+1 (16 pairs per tile).
+  auto exp_pair = [&](const f32x16 (&sc)[2], bf16x8 (&pf)[4], float shift, int q) __attribute__((always_inline)) {
+    const int e = 2 * q, mb = e >> 4, v = e & 15;
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v + 1], a.scale_log2, shift));
+    l_run += p0;
+    l_part += p1;
+    bf16x2 pk;
+    pk[0] = (__bf16)p0;
+    pk[1] = (__bf16)p1;
+    {  // keep the arithmetic in this slice: pure values are otherwise free to sink to their first use
+      uint32_t bits = __builtin_bit_cast(uint32_t, pk);
+      asm volatile("" : "+v"(bits), "+v"(l_run), "+v"(l_part));
+      pk = __builtin_bit_cast(bf16x2, bits);
     }
+    pf[2 * mb + (v >> 3)][v & 7] = pk[0];
+    pf[2 * mb + (v >> 3)][(v & 7) + 1] = pk[1];
   };
+  // The vector unit keeps up with the matrix pipe only if its work is spread evenly over the MFMAs of
+  // BOTH products: about one probability per MFMA.  Pairs 0..NPA-1 of tile t are computed beside the
+  // first product of tile t+1; the rest beside the second product of tile t, each just before the
+  // k-step that consumes it (k-step ks of the second product reads pairs 4ks..4ks+3).
+  constexpr int NPA = 10;
+  constexpr int BSTRIDE = NB / 8;             // slots of the second product per late pair
 
   // One step per tile t (MORE: a tile t+1 exists):
   //   wait + barrier | fire V(t+1), K(t+2)
@@ -410,52 +478,62 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // The order inside the two phases is fixed by hand (scheduling fences between the slices): the
   // matrix pipe executes one MFMA while the vector unit works through the slice behind it.
   float shift_cur = 0.f;                      // exponent constant of the tile whose scores are current
-  auto step = [&](auto more_tag, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
-    constexpr bool MORE = decltype(more_tag)::value;
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's K(t+1), V(t) have landed
-    __syncthreads();                          // ... and everyone else's; buffers of K(t), V(t-1) are free
-    if (MORE) fire_v(t + 1);
-    const bool k2 = MORE && t + 2 < total_tiles;
-    if (k2) { fire_k(t + 2); k_plan_to_v(); }
-    const bool k3 = MORE && t + 3 < total_tiles;
-    const uint32_t flip_n = ((t + 1) & 1) ? (uint32_t)TILEB : 0u;
-    const uint32_t flip_c = (t & 1) ? (uint32_t)TILEB : 0u;
+  // Tiles past the end of the row are planned and requested like any other (null tiles: their loads
+  // are all out of range and fetch nothing) and the scores of the first of them are computed and
+  // dropped, so the step has one shape and no conditions besides the two rare paths.
+  auto step = [&](auto parity_tag, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(parity_tag)::value;      // t & 1, known at each call site
+    constexpr bool MORE = true, k3 = true, k4 = true;
+    const bool has_next = t + 1 < total_tiles;
+    wait_loads(true);                         // K(t+1): only V(t) and K(t+2) were requested after it
+    wg_barrier();                             // ... everyone's part of it; the buffer of V(t-1) is free
+    fire_v(t + 1);
+    constexpr uint32_t flip_n = PAR ? 0u : (uint32_t)TILEB;
+    constexpr uint32_t flip_c = PAR ? (uint32_t)TILEB : 0u;
     bf16x8 pf[4];
     bf16x8 fr[4];                             // rolling operand fragments, requested PF MFMAs ahead
-    constexpr int PF = 3;
+    constexpr int PF = 2;
     __builtin_amdgcn_sched_barrier(0);
     if (MORE) {
 #pragma unroll
-      for (int j = 0; j < PF; ++j) fr[j] = read_k(j, flip_n);
+      for (int j = 0; j < PF; ++j) read_k_asm(fr[j], j, (int)flip_n);
     }
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
       if (MORE) {
-        if (j + PF < NA) fr[(j + PF) & 3] = read_k(j + PF, flip_n);
+        if (j + PF < NA) read_k_asm(fr[(j + PF) & 3], j + PF, (int)flip_n);
         const int mb = j & 1, ks = j >> 1;
+        take_k(fr[j & 3], (j + PF < NA ? j + PF : NA - 1) - j);
         sn[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], qf[ks], ks == 0 ? zero16 : sn[mb], 0, 0, 0);
       }
-      exp_chunk(sc, pf, shift_cur, j);
+      if (j == NA / 2 && k4) plan_read();
+#pragma unroll
+      for (int q = (j * NPA) / NA; q < ((j + 1) * NPA) / NA; ++q) exp_pair(sc, pf, shift_cur, q);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (MORE) {
-      if ((spec_ring >> ((t + 1) & 7)) & 1u) fixup_special(sn, t + 1);
-      if (k3) plan_begin();
-    }
+    if (k4) plan_resolve();
+    wait_loads(true);                         // V(t): only K(t+2) and V(t+1) were requested after it
+    wg_barrier();                             // ... everyone's part of it; the buffer of K(t+1) is free
+    if (k3) fire_k(t + 3);
+    rotate_plans();
+    if (has_next && ((spec_ring >> ((t + 1) & 7)) & 1u)) fixup_special(sn, t + 1);
     __builtin_amdgcn_sched_barrier(0);
+    s16x4 vlo[4], vhi[4];
 #pragma unroll
-    for (int j = 0; j < PF; ++j) fr[j] = read_vt(j, flip_c);
+    for (int j = 0; j < PF; ++j) read_vt(vlo[j], vhi[j], j, (int)flip_c);
     float rawmax = -INFINITY;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      if (j + PF < NB) fr[(j + PF) & 3] = read_vt(j + PF, flip_c);
+      if (j + PF < NB) read_vt(vlo[(j + PF) & 3], vhi[(j + PF) & 3], j + PF, (int)flip_c);
       const int md = j % (D / 32), ks = j / (D / 32);
-      oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], pf[ks], oacc[md], 0, 0, 0);
-      if (MORE) {
-        if (k3) {
+      const bf16x8 vfrag = take_vt(vlo[j & 3], vhi[j & 3], 2 * ((j + PF < NB ? j + PF : NB - 1) - j));
+      oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[ks], oacc[md], 0, 0, 0);
+      if (j % BSTRIDE == 0 && NPA + j / BSTRIDE < 16) exp_pair(sc, pf, shift_cur, NPA + j / BSTRIDE);
+      if (k4) {
 #pragma unroll
-          for (int k = j; k < RI; k += NB) plan_part(k);
-        }
+        for (int k = j; k < RI; k += NB) plan_part(k);
+      }
+      if (MORE) {
 #pragma unroll
         for (int u = 0; u < MPC; ++u) {
           const int e = (j * MPC + u) * 2, mb = e >> 4, v = e & 15;
@@ -465,10 +543,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (MORE) {
-      if (k3) plan_end(t + 3);
-      shift_cur = advance_max(rawmax, t + 1);
-    }
+    if (k4) plan_end(t + 4);
+    if (has_next) shift_cur = advance_max(rawmax, t + 1);
   };
 
   f32x16 sA[2], sB[2];
@@ -478,29 +554,32 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     for (int v = 0; v < 16; ++v) { sA[mb][v] = 0.f; sB[mb][v] = 0.f; }
   __syncthreads();                           // block list is in LDS
   if (total_tiles > 0) {
-    // prologue: plans of tiles 0..2, loads of K(0), V(0), K(1), scores and maximum of tile 0
-    plan_begin();
+    // prologue: K(0), K(1), V(0) requested, scores of tile 0, then K(2); plans of tiles 0..3
+    auto plan_whole = [&](int tp) __attribute__((always_inline)) {
+      plan_read();
+      plan_resolve();
 #pragma unroll
-    for (int k = 0; k < RI; ++k) plan_part(k);
-    plan_end(0);
+      for (int k = 0; k < RI; ++k) plan_part(k);
+      plan_end(tp);
+    };
+    plan_whole(0);
     fire_k(0);
-    k_plan_to_v();
-    if (total_tiles > 1) {
-      plan_begin();
-#pragma unroll
-      for (int k = 0; k < RI; ++k) plan_part(k);
-      plan_end(1);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
+    rotate_plans();                          // V2 = plan 0
+    rotate_plans();                          // V1 = plan 0
     fire_v(0);
-    if (total_tiles > 1) { fire_k(1); k_plan_to_v(); }
-    if (total_tiles > 2) {
-      plan_begin();
+    plan_whole(1);
+    fire_k(1);
 #pragma unroll
-      for (int k = 0; k < RI; ++k) plan_part(k);
-      plan_end(2);
-    }
+    for (int k = 0; k < RI; ++k) planV1[k] = planK[k];     // V1 = plan 1
+    planV1_vbase = planK_vbase;
+    planV1_nrec = planK_nrec;
+    plan_whole(2);                           // K(2) goes out once the scores of tile 0 are done
+#pragma unroll
+    for (int k = 0; k < RI; ++k) planV2[k] = planK[k];     // V2 = plan 2
+    planV2_vbase = planK_vbase;
+    planV2_nrec = planK_nrec;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    wg_barrier();
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
       const int mb = j & 1, ks = j >> 1;
@@ -513,28 +592,29 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
       for (int v = 0; v < 16; ++v) rawmax = fmaxf(rawmax, sA[mb][v]);
     shift_cur = advance_max(rawmax, 0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    wg_barrier();                            // every wavefront has read K(0): its buffer takes K(2)
+    fire_k(2);
+    plan_whole(3);
   }
   {
-    const std::true_type more;
-    const std::false_type last;
+    const std::integral_constant<int, 0> even;
+    const std::integral_constant<int, 1> odd;
     int t = 0;
-    for (; t + 2 < total_tiles; t += 2) {
-      step(more, sA, sB, t);
-      step(more, sB, sA, t + 1);
+    for (; t + 1 < total_tiles; t += 2) {
+      step(even, sA, sB, t);
+      step(odd, sB, sA, t + 1);
     }
-    if (t + 1 < total_tiles) {
-      step(more, sA, sB, t);
-      step(last, sB, sA, t + 1);
-    } else if (t < total_tiles) {
-      step(last, sA, sB, t);
-    }
+    if (t < total_tiles) step(even, sA, sB, t);
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // the null tiles still in flight write LDS: drain before the workgroup ends
   }
 
   // ---- epilogue: O = o / l ; lane (row, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
   {
     float l_lo, l_hi;
+    l_run += l_part;
     both_halves(l_run, l_lo, l_hi);
-    const float l_tot = l_lo + l_hi;
+    const float l_tot = l_lo + l_hi;   // (l_run already holds both partial sums)
     if (qrow < row_end) {
       const float inv = 1.f / l_tot;
       bf16_t* op = O + (qhead * a.N + qrow) * D;
@@ -553,10 +633,10 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 }
 
 size_t attn_mfma_smem_bytes(int d, int nk) {
-  return 4 * (size_t)BN * d * sizeof(bf16_t) + (((size_t)nk * 2 + 15) & ~(size_t)15);
+  return 4 * (size_t)BN * d * sizeof(bf16_t) + 4 * 512 + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
-template <int D, int NW>
+template <int D, int NW, bool SC>
 static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                                 const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                                 hipStream_t s) {
@@ -571,7 +651,7 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
   const size_t smem = attn_mfma_smem_bytes(D, pl.nk);
-  auto kern = attn_mfma_kernel<D, NW>;
+  auto kern = attn_mfma_kernel<D, NW, SC>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)smem);
   if (e != hipSuccess) return e;
@@ -581,21 +661,31 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   return hipGetLastError();
 }
 
+template <int D, int NW>
+static hipError_t launch_mfma_d(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
+                                const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
+                                hipStream_t s) {
+  constexpr int RPI = 64 / (D / 8);           // tile rows per wave-wide 16 B/lane load
+  const bool blocks_cover_a_load = (pl.bk >> (pl.H - 1)) >= RPI;
+  return blocks_cover_a_load ? launch_mfma_t<D, NW, true>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s)
+                             : launch_mfma_t<D, NW, false>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+}
+
 hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                             const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                             hipStream_t s) {
   const int rows = pl.bq < 128 ? pl.bq : 128;   // rows per workgroup
   if (pl.d == 128) {
     switch (rows) {
-      case 32: return launch_mfma_t<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_t<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_t<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_d<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_d<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_d<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   } else if (pl.d == 64) {
     switch (rows) {
-      case 32: return launch_mfma_t<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_t<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_t<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_d<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 64: return launch_mfma_d<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 128: return launch_mfma_d<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
     }
   }
   return hipErrorInvalidValue;
