@@ -6,23 +6,29 @@
 // b_k/2^(h-1) tokens is split over several tiles or merged with its neighbours), so every tile but
 // the last of a level feeds full 32x32x16 MFMAs and the (h-1) ln 2 bias is one constant per tile.
 //
-// One workgroup = one slice of up to 128 query rows.  A wavefront owns QB groups of 32 rows.  QB = 2
-// lets every K / V^T fragment read from LDS feed two MFMAs (half the LDS traffic per FLOP) but needs
-// one wavefront per SIMD with a 512-register budget; measured at d = 64 it is 1.5x SLOWER than
-// QB = 1 with two wavefronts per SIMD, so QB = 1 is what the launcher picks.  Per tile:
-//   K/V rows go HBM/L2 -> LDS directly (global_load_lds, 16 B per lane), double-buffered, one
-//   barrier per tile; the 16-byte chunks of a row are XOR-swizzled on the way in so that the MFMA
-//   operand reads are bank-conflict free without padding.
+// One workgroup = one slice of up to 128 query rows, one wavefront per 32 rows, two workgroups per
+// compute unit (two wavefronts per SIMD, ~256 registers each).  Per tile:
+//   K/V rows go HBM/L2 -> LDS directly (buffer_load ... lds, 16 B per lane; the descriptor's range
+//   check drops rows past the end of the unpadded level-1 arrays), two buffers each; a tile's K rows
+//   are requested one and a half steps before its first product, its V rows one and a half steps
+//   before its second product.  The 16-byte chunks of a row are XOR-swizzled on the way in so that
+//   the MFMA operand reads are bank-conflict free without padding.
 //   S^T = K_tile Q^T        (A = K rows from LDS, B = Q fragments held in registers)
 //   online softmax in the log2 domain; the accumulator layout of S^T puts ONE query row in each
 //   lane, so row max / row sum are in-lane reductions plus one exchange with lane^32, and the
 //   bfloat16 P^T fragments are already in the B-operand layout of the second product
 //   O^T += V_tile^T P^T     (A = V^T, read from the row-major V tile with the transposing LDS load)
-// The step is software-pipelined inside the wavefront: the S^T MFMAs of tile t+1 are issued before
-// the softmax of tile t, so the matrix pipe works through them while the vector unit does the
-// exponentials.  The running maximum is only advanced when it grows by more than 2^8 (the
-// accumulators stay well inside fp32 range), which removes the per-tile rescale of O from the
-// common path.
+// A step handles the first product of tile t+1 and the second product of tile t.  With two
+// wavefronts per SIMD the kernel is bound by how fast a wavefront can issue instructions, so the
+// order inside a step is fixed by hand: every MFMA is followed by a slice of the vector work
+// (about one probability per MFMA over both products, the next tile's maximum, the plan of a
+// later tile's loads), and all bookkeeping that can be wave-uniform lives in scalar registers.
+// The running maximum is only advanced when it grows by more than 2^8 (the accumulators stay well
+// inside fp32 range), which removes the per-tile rescale of O from the common path.
+// Three things the compiler would otherwise get wrong are taken out of its hands, each explained
+// where it happens: waits for LDS reads next to direct-to-LDS loads (tile reads are assembly with
+// counted waits), the fence of __syncthreads (plain s_barrier plus counted vmcnt waits), and pure
+// arithmetic drifting out of its slice (empty asm pins).
 #include <type_traits>
 
 #include "psa_dev.h"
