@@ -81,9 +81,9 @@ def measured_traffic(w, budget, kernel_prefix: str):
     return None
 
 
-def cpu_baseline(w, budget, Q, K, V, n_heads: int = 2):
-    """The oracle as it stands on this host: one head's pyramid, importance and allocation, and the
-    attention of a few query blocks of that head; extrapolated to the whole workload."""
+def cpu_baseline(w, budget, Q, K, V, n_heads: int = 3):
+    """The oracle as it stands on this host: pyramid, importance, allocation and attention (every query
+    block) of the first `n_heads` heads, extrapolated to the whole workload."""
     import dataclasses
 
     import synth_inputs as si
