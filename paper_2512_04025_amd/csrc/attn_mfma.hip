@@ -205,20 +205,14 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // at its start, plan_resolve (ids to scalar registers, irregularity test) once the first product is
   // out, plan_part (offsets; arithmetic only) between the MFMAs of the second product, plan_end.
   int plan_jl = 0;                            // block id of tile row `lane`
-  int plan_js[RI];                            // wave-uniform block id of each load
+  uint32_t plan_off = 0;                      // byte offset of the source row of tile row `lane`
   auto plan_read = [&]() __attribute__((always_inline)) {
     const int g0 = ld_tl << 6;
     {
       const int e = (g0 + lane) >> ls.lg_th;
       plan_jl = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
     }
-    if (SC) {
-#pragma unroll
-      for (int k = 0; k < RI; ++k) {
-        const int e = (g0 + (k * NW + wave) * RPI) >> ls.lg_th;                 // scalar
-        plan_jj[k] = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];   // same address in every lane
-      }
-    } else {
+    if (!SC) {
 #pragma unroll
       for (int k = 0; k < RI; ++k) {
         const int e = (g0 + (k * NW + wave) * RPI + lrow) >> ls.lg_th;
@@ -227,21 +221,16 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
   };
   auto plan_resolve = [&]() __attribute__((always_inline)) {
-    {  // the whole tile, one row per lane: is any row past the kept blocks, the ragged tail or the causal limit?
-      const int g = (ld_tl << 6) + lane, e = g >> ls.lg_th;
-      const int prow = (plan_jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
-      plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
-    }
-    if (SC) {
-#pragma unroll
-      for (int k = 0; k < RI; ++k) plan_js[k] = __builtin_amdgcn_readfirstlane(plan_jj[k]);
-    }
+    // the whole tile, one row per lane: its source row, and whether any row is past the kept blocks,
+    // the ragged tail or the causal limit
+    const int g = (ld_tl << 6) + lane, e = g >> ls.lg_th;
+    const int prow = (plan_jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
+    plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
+    plan_off = (uint32_t)prow * (uint32_t)ROWB;
   };
   auto plan_part = [&](int k) __attribute__((always_inline)) {
-    if (SC) {
-      const int g = (ld_tl << 6) + (k * NW + wave) * RPI;        // first row of this load in the level's token stream
-      const int prow0 = (plan_js[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
-      planK[k] = (uint32_t)prow0 * (uint32_t)ROWB;               // wave-uniform: stays in a scalar register
+    if (SC) {    // the first row of the load decides (the others follow it inside the same block): one lane read
+      planK[k] = (uint32_t)__builtin_amdgcn_readlane((int)plan_off, (k * NW + wave) * RPI);
     } else {
       const int g = (ld_tl << 6) + (k * NW + wave) * RPI + lrow;   // position in the level's token stream
       const int prow = (plan_jj[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));   // row in the level-h array
