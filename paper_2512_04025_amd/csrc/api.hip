@@ -61,6 +61,7 @@ int make_plan(const psa_params* p, Plan* o) {
   o->off_qrep = s;   s += align256(heads_q * o->nq * o->sq * o->d * o->esize);
   o->off_krep = s;   s += o->krep_is_pyramid ? 0 : align256((size_t)o->B * o->Hkv * o->nk * o->sk * o->d * o->esize);
   o->off_scores = s; s += align256(rows_q * o->nk * sizeof(float));
+  o->off_part = s;   s += align256(heads_q * o->nq * o->sq * 8 * 2 * sizeof(float));   // up to 8 key slices x (max, sum)
   o->off_rowcnt = s; s += align256(rows_q * ROWCNT_STRIDE * sizeof(uint32_t));
   o->off_idx = s;    s += align256(rows_q * o->nk * sizeof(uint16_t));
   o->off_cnt = s;    s += align256(rows_q * CNT_STRIDE * sizeof(int32_t));
@@ -162,7 +163,7 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
       krep = kr;
     }
     float* sdst = scores_out ? scores_out : reinterpret_cast<float*>(at(scratch, pl.off_scores));
-    if (launch_importance(pl, qrep, krep, sdst, s) != hipSuccess) return PSA_ELAUNCH;
+    if (launch_importance(pl, qrep, krep, at(scratch, pl.off_part), sdst, s) != hipSuccess) return PSA_ELAUNCH;
     scores = sdst;
   } else if (scores_out && scores_out != scores_in) {
     const size_t bytes = (size_t)pl.B * pl.Hq * pl.nq * pl.nk * sizeof(float);

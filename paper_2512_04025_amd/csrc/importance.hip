@@ -9,6 +9,8 @@
 // The softmax is done in one sweep over the keys: per (row, key block) the kernel keeps the block's
 // maximum logit and sum of exponentials relative to it; the row max / row sum and the normalised
 // tile statistics follow from those, so no logit is stored or recomputed.
+#include <type_traits>
+
 #include "psa_dev.h"
 #include "psa_internal.h"
 
@@ -215,216 +217,371 @@ static hipError_t launch_imp_t(const Plan& pl, const void* Qrep, const void* Kre
 }
 
 
-// ------------------------------------------------------------------------------------------------
-// Matrix-core version for bfloat16 with 8 representatives per query block and per key block (the
-// default: pooled keys are pyramid level H).  One workgroup = 64 representative query rows (8 query
-// blocks); its 4 wavefronts split the representative keys into 4 contiguous ranges.  The logits are
-// computed as S^T = K~ Q~^T with 32x32x16 MFMAs, so a lane holds ONE query row and, per 32-key MFMA
-// block, 16 logits = 4 key blocks x 4 keys (the other 4 keys of each block sit in lane^32).
-// Two sweeps over the keys: the first builds the row maximum and row sum of exponentials (merged
-// across the 4 wavefronts through LDS), the second recomputes the logits and reduces the normalised
-// weights to one number per (query block, key block): max or mean over the 8 x 8 sub-tile.  The
-// logits are recomputed instead of stored: they cost 2 * 8 * 8 * d FLOPs per score, the matrix
-// cores are otherwise idle, and nothing but S ever goes to memory.
-struct ImpMfmaArgs {
-  int N, Hq, Hkv, nq, nk, bq, bk, mode, causal, est_pool;
+// ---------------------------------------------------------------------------------------------
+// Matrix-core version for bfloat16 with s_q = s_k = 8 (Eq. 4; mean variant of App. B.2).
+//
+// Two launches of one kernel.  A workgroup takes 128 representative query rows (4 wavefronts x 32)
+// and one of `ksplit` slices of the representative keys, so a small problem still fills the chip;
+// the key slice streams through LDS in tiles of 64 keys (direct-to-LDS loads into a ring of four
+// tiles, shared by the four wavefronts, chunks XOR-swizzled as in the attention kernel) and
+// S^T = K~ Q~^T runs on 32x32x16 MFMAs with one query row per lane.
+//   sweep 1: per row and key slice, the running maximum and the sum of exponentials (log2 domain)
+//   sweep 2: the slices' partial results merged into lse = m + log2(l) per row; the logits are
+//            recomputed and w = 2^(scale*dot - lse) is pooled over every 8x8 sub-tile.  For max
+//            pooling the monotone exp2 is applied once, after the maximum.
+// Cross-lane steps use the half-swap and lane-permuting operands instead of LDS shuffles.
+constexpr int IMP_MAX_SPLIT = 8;
+
+struct ImpTileArgs {
+  int N, Hq, Hkv, nq, nk, bq, bk, mode, causal, est_pool, ksplit;
   float scale_log2;
 };
 
-template <int D>
-__global__ __launch_bounds__(256) void importance_mfma_kernel(const bf16_t* __restrict__ Qrep,
-                                                              const bf16_t* __restrict__ Krep,
-                                                              float* __restrict__ S, ImpMfmaArgs a) {
-  constexpr int SQ = 8, SK = 8, KS = D / 16;
-  constexpr int QB = 2;                            // 32-row groups per wavefront: every K~ fragment feeds QB MFMAs
-  __shared__ float part[4][QB][32][2];             // per wavefront: row max (log2 domain), row sum
+typedef __attribute__((address_space(3))) void imp_lds_void;
+
+template <int D, int SWEEP>
+__global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
+                                                               const bf16_t* __restrict__ Krep,
+                                                               float2* __restrict__ part, float* __restrict__ S,
+                                                               ImpTileArgs a) {
+  constexpr int SQ = 8, SK = 8, KS = D / 16, BN = 64, NW = 4, NSLOT = 4;
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NINST = BN / RPI, RI = NINST / NW, RP256 = 16 / CPR;
+  constexpr int ROWB = D * 2, TILEB = BN * ROWB;
+  constexpr int KP = 16 / (NW * RPI) > 1 ? 16 / (NW * RPI) : 1;
+  constexpr int STAGE_TILES = 16;              // tiles of scores staged in LDS between write-outs (sweep 2)
+  extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];
+  float* stage = reinterpret_cast<float*>(ring + NSLOT * TILEB);   // [16][8 * STAGE_TILES]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
-  const int rg = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int rg = blockIdx.x, split = blockIdx.y, head = blockIdx.z;
+  const int b = head / a.Hq, hq = head % a.Hq;
   const int hk = hq / (a.Hq / a.Hkv);
   const int nrows = a.nq * SQ, nkeys = a.nk * SK;
   const bf16_t* qbase = Qrep + (((int64_t)b * a.Hq + hq) * nrows) * D;
-  const bf16_t* kbase = Krep + (((int64_t)b * a.Hkv + hk) * (int64_t)nkeys) * D;
+  const char* kbase = reinterpret_cast<const char*>(Krep + (((int64_t)b * a.Hkv + hk) * (int64_t)nkeys) * D);
 
-  int row[QB], qi[QB], qpos[QB];
-  bf16x8 qf[QB][KS];
+  const int row = rg * 128 + wave * 32 + l32;    // representative query row of this lane
+  const int qi = row / SQ;                       // its query block
+  const int qpos = row < nrows ? rep_pos(a.mode, qi, row % SQ, a.bq, SQ, a.N) : -1;
+  bf16x8 qf[KS];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    row[qb] = (rg * QB + qb) * 32 + l32;           // representative query row of this lane
-    qi[qb] = row[qb] / SQ;                         // its query block
-    qpos[qb] = row[qb] < nrows ? rep_pos(a.mode, qi[qb], row[qb] % SQ, a.bq, SQ, a.N) : -1;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (row[qb] < nrows) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)row[qb] * D + ks * 16 + hf * 8);
-      qf[qb][ks] = __builtin_bit_cast(bf16x8, v);
-    }
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < nrows) v = *reinterpret_cast<const u32x4*>(qbase + (int64_t)row * D + ks * 16 + hf * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8, v);
   }
 
-  // this wavefront's range of 32-key MFMA blocks
-  const int nb32 = (nkeys + 31) >> 5;
-  const int per = (nb32 + 3) >> 2;
-  const int blk_lo = wave * per;
-  const int blk_hi = blk_lo + per < nb32 ? blk_lo + per : nb32;
+  // this workgroup's tiles of 64 keys
+  const int ntile_all = (nkeys + BN - 1) / BN;
+  const int per = (ntile_all + a.ksplit - 1) / a.ksplit;
+  const int t_lo = split * per;
+  int nt = (t_lo + per < ntile_all ? t_lo + per : ntile_all) - t_lo;
+  nt = nt > 0 ? nt : 0;
 
-  auto load_k = [&](bf16x8 (&kf)[KS], int blk) __attribute__((always_inline)) {
-    int c = blk * 32 + l32;
-    c = c < nkeys ? c : nkeys - 1;                 // stay in bounds; such keys are masked below
-    const bf16_t* kp = kbase + (int64_t)c * D + hf * 8;
+  {  // ring starts as zeros: a lane whose key row is out of range leaves its LDS slot alone
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int x = tid * 16; x < NSLOT * TILEB; x += 256 * 16) *reinterpret_cast<u32x4*>(ring + x) = z;
+  }
+  const int lrow = lane / CPR, lpos = lane % CPR;
+  uint32_t klane[KP];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(kp + ks * 16));
+  for (int k = 0; k < KP; ++k) {
+    const int r = (k * NW + wave) * RPI + lrow;
+    klane[k] = (uint32_t)(lrow * ROWB) + (uint32_t)((lpos ^ ((r / RP256) % CPR)) << 4);
+  }
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)kbase, 0, (int)((uint32_t)nkeys * (uint32_t)ROWB), 0x00020000);
+  auto fire = [&](int tt) __attribute__((always_inline)) {       // tile tt of this slice -> ring slot tt % NSLOT
+    const uint32_t tile_off = (uint32_t)(t_lo + tt) * (uint32_t)TILEB;
+#pragma unroll
+    for (int k = 0; k < RI; ++k)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (imp_lds_void*)(ring + (tt % NSLOT) * TILEB + (k * NW + wave) * RPI * ROWB), 16,
+                                               (int)(tile_off + (uint32_t)((k * NW + wave) * RPI * ROWB) + klane[k % KP]), 0, 0, 0);
   };
-  // logits of one MFMA block in the log2 domain, masked; t[qb][v] is key blk*32 + (v/4)*8 + hf*4 + v%4
-  auto logits = [&](const bf16x8 (&kf)[KS], int blk, float (&t)[QB][16]) __attribute__((always_inline)) {
-    f32x16 acc[QB];
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  asm volatile("s_barrier" ::: "memory");      // zeros are in place before the first loads land
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+  for (int tt = 0; tt < NSLOT - 1; ++tt)
+    if (tt < nt) fire(tt);
+
+  // K~ operand reads: row mb*32 + l32 of the tile, chunk (2 ks + hf) ^ swizzle(row).  Written as
+  // assembly with counted waits: ordinary loads next to direct-to-LDS loads make the compiler wait
+  // for tiles that are still on their way into OTHER ring slots.
+  uint32_t kaddr[KS];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        if (ks == 0) {
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], zero, 0, 0, 0);
-        } else {
-          acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[qb][ks], acc[qb], 0, 0, 0);
-        }
-      }
-    const int gk = a.bk / SK;
-    // fast path: every key of the block is valid and nothing is causally hidden
-    const bool plain = !a.causal && (a.mode == PSA_REP_STRIDED ? blk * 32 + 32 <= nkeys
-                                                               : (int64_t)(blk * 32 + 31) * gk < a.N);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      if (plain) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) t[qb][v] = qpos[qb] >= 0 ? acc[qb][v] * a.scale_log2 : -INFINITY;
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int c = blk * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-          const int kpos = c < nkeys ? rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N) : -1;
-          const bool dead = kpos < 0 || qpos[qb] < 0 || (a.causal && kpos > qpos[qb]);
-          t[qb][v] = dead ? -INFINITY : acc[qb][v] * a.scale_log2;
-        }
+  for (int ks = 0; ks < KS; ++ks)
+    kaddr[ks] = (uint32_t)(l32 * ROWB + ((hf ^ ((l32 / RP256) % CPR)) << 4)) ^ (uint32_t)(ks << 5);
+
+  const bool rows_full = rg * 128 + 128 <= nrows;
+  const int gk = a.bk / SK;
+  auto is_plain = [&](int tile) __attribute__((always_inline)) {   // all 64 keys and all rows valid, nothing hidden
+    return rows_full && !a.causal && (a.mode == PSA_REP_STRIDED ? tile * BN + BN <= nkeys
+                                                                : (int64_t)(tile * BN + BN - 1) * gk < a.N);
+  };
+  auto both_halves = [&](float x, float& p, float& q) __attribute__((always_inline)) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    uint32_t u2 = u;
+    asm volatile("" : "+v"(u2));                 // two distinct operands and laundered results: given one
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u2, false, false);   // value twice the optimiser
+    uint32_t r0 = r[0], r1 = r[1];               // treats the two results as equal
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    p = __builtin_bit_cast(float, r0);
+    q = __builtin_bit_cast(float, r1);
+  };
+  // the 8 representative rows of a query block sit in 8 consecutive lanes
+  auto lane_xor1 = [&](float x) __attribute__((always_inline)) {
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, true));
+  };
+  auto lane_xor2 = [&](float x) __attribute__((always_inline)) {
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, true));
+  };
+  auto lane_mirror8 = [&](float x) __attribute__((always_inline)) {   // lane 7 - i of the group of 8
+    const int v = __builtin_bit_cast(int, x);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, true));
+  };
+
+  float m = -INFINITY, l = 0.f, lse = INFINITY;
+  if (SWEEP == 2) {
+    float mrow = -INFINITY, lrow = 0.f;
+    if (row < nrows) {
+      const float2* pr = part + (((int64_t)b * a.Hq + hq) * nrows + row) * IMP_MAX_SPLIT;
+      for (int s2 = 0; s2 < a.ksplit; ++s2) mrow = fmaxf(mrow, pr[s2].x);
+      for (int s2 = 0; s2 < a.ksplit; ++s2) {
+        const float2 v = pr[s2];
+        if (v.x != -INFINITY) lrow += v.y * __builtin_amdgcn_exp2f(v.x - mrow);
       }
     }
-  };
+    lse = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;          // no visible key: all weights 0
+  }
+  float* out = S + (((int64_t)b * a.Hq + hq) * a.nq) * (int64_t)a.nk;
 
-  // ---- sweep 1: row max and row sum (online, in the log2 domain)
-  float m[QB], l[QB];
+  // one tile: acc[mb][v] = dot of this lane's row with key tile*64 + mb*32 + (v/4)*8 + hf*4 + v%4
+  auto tile_step = [&](auto slot_tag, int tt) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    const int tile = t_lo + tt;
+    bf16x8 f0[KS], f1[KS];
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
-  {
-    bf16x8 ka[KS], kb[KS];
-    auto stat = [&](const bf16x8 (&kf)[KS], int blk) __attribute__((always_inline)) {
-      float t[QB][16];
-      logits(kf, blk, t);
+    for (int ks = 0; ks < KS; ++ks)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f0[ks]) : "v"(kaddr[ks]), "n"(SLOT * TILEB));
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float bm = t[qb][0];
+    for (int ks = 0; ks < KS; ++ks)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f1[ks]) : "v"(kaddr[ks]), "n"(SLOT * TILEB + 32 * ROWB));
+    f32x16 acc[2];
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 1; v < 16; ++v) bm = fmaxf(bm, t[qb][v]);
-        bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-        const float mn = fmaxf(m[qb], bm);
+    for (int ks = 0; ks < KS; ++ks) {
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f0[ks]) : "n"(2 * KS - 1 - ks));
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0[ks], qf[ks], ks == 0 ? zero : acc[0], 0, 0, 0);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f1[ks]) : "n"(KS - 1 - ks));
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1[ks], qf[ks], ks == 0 ? zero : acc[1], 0, 0, 0);
+    }
+    const bool plain = is_plain(tile);
+    // logits in the log2 domain (sweep 2: minus lse), dead keys / rows / causally hidden keys at -inf
+    float x[2][16];
+    if (!plain) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int c = tile * BN + mb * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+          const int kpos = c < nkeys ? rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N) : -1;
+          const bool dead = kpos < 0 || qpos < 0 || (a.causal && kpos > qpos);
+          x[mb][v] = dead ? -INFINITY : (SWEEP == 1 ? acc[mb][v] * a.scale_log2 : fmaf(acc[mb][v], a.scale_log2, -lse));
+        }
+    }
+    if (SWEEP == 1) {
+      if (plain) {
+        // the running maximum only moves when it would grow by more than 2^8: the common path is one
+        // fused multiply-add, one exp2 and one add per logit
+        float bm = fmaxf(acc[0][0], acc[1][0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) bm = __builtin_fmaxf(bm, __builtin_fmaxf(acc[0][v], acc[1][v]));   // v_max3
+        bm *= a.scale_log2;
+        float p, q;
+        both_halves(bm, p, q);
+        bm = fmaxf(p, q);
+        if (__any(bm - m > 8.0f)) {
+          const float mn = fmaxf(m, bm);
+          l *= __builtin_amdgcn_exp2f(m - mn);     // m = -inf: l is 0 and stays 0
+          m = mn;
+        }
+        const float neg_m = -m;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s0 += __builtin_amdgcn_exp2f(fmaf(acc[0][v], a.scale_log2, neg_m));
+          s1 += __builtin_amdgcn_exp2f(fmaf(acc[1][v], a.scale_log2, neg_m));
+        }
+        l += s0 + s1;
+      } else {
+        float bm = -INFINITY;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) bm = fmaxf(bm, x[mb][v]);
+        float p, q;
+        both_halves(bm, p, q);
+        bm = fmaxf(p, q);
+        const float mn = fmaxf(m, bm);
         if (mn != -INFINITY) {
           float sum = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(t[qb][v] - mn);
-          l[qb] = l[qb] * __builtin_amdgcn_exp2f(m[qb] - mn) + sum;
-          m[qb] = mn;
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(x[mb][v] - mn);
+          l = l * __builtin_amdgcn_exp2f(m - mn) + sum;
+          m = mn;
         }
       }
-    };
-    if (blk_lo < blk_hi) load_k(ka, blk_lo);
-    for (int blk = blk_lo; blk < blk_hi; blk += 2) {
-      if (blk + 1 < blk_hi) load_k(kb, blk + 1);
-      stat(ka, blk);
-      if (blk + 1 < blk_hi) {
-        if (blk + 2 < blk_hi) load_k(ka, blk + 2);
-        stat(kb, blk + 1);
+    } else {
+      // per lane: 8 partial results (2 halves x 4 key blocks), each over the 4 keys this lane holds.
+      // The half swap pairs value g of the first half with value g of the second: afterwards lanes
+      // 0..31 own the 4 key blocks of the first half (both lane halves folded), lanes 32..63 those
+      // of the second; then the 8 rows of a query block (8 consecutive lanes) are folded.
+      const bool maxp = a.est_pool == PSA_EST_MAX;
+      float w[4];
+      auto fold = [&](auto max_tag, const float (&r)[2][4]) __attribute__((always_inline)) {
+        constexpr bool MAXP = decltype(max_tag)::value;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint32_t u0 = __builtin_bit_cast(uint32_t, r[0][g]), u1 = __builtin_bit_cast(uint32_t, r[1][g]);
+          const auto sw = __builtin_amdgcn_permlane32_swap(u0, u1, false, false);   // (r0.lo, r1.lo), (r0.hi, r1.hi)
+          uint32_t s0 = sw[0], s1 = sw[1];
+          asm volatile("" : "+v"(s0), "+v"(s1));
+          const float p = __builtin_bit_cast(float, s0), q = __builtin_bit_cast(float, s1);
+          float v = MAXP ? fmaxf(p, q) : p + q;
+          v = MAXP ? fmaxf(v, lane_xor1(v)) : v + lane_xor1(v);
+          v = MAXP ? fmaxf(v, lane_xor2(v)) : v + lane_xor2(v);
+          v = MAXP ? fmaxf(v, lane_mirror8(v)) : v + lane_mirror8(v);
+          w[g] = MAXP ? __builtin_amdgcn_exp2f(v) : v * (1.f / (float)(SQ * SK));
+        }
+      };
+      float r[2][4];
+      if (plain && maxp) {          // the common case: max of the raw dots first, one fused multiply-add per key block
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            r[mb][g] = fmaf(fmaxf(fmaxf(acc[mb][4 * g], acc[mb][4 * g + 1]), fmaxf(acc[mb][4 * g + 2], acc[mb][4 * g + 3])),
+                            a.scale_log2, -lse);
+        fold(std::true_type{}, r);
+      } else {
+        if (plain) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) x[mb][v] = fmaf(acc[mb][v], a.scale_log2, -lse);
+        }
+        if (maxp) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              r[mb][g] = fmaxf(fmaxf(x[mb][4 * g], x[mb][4 * g + 1]), fmaxf(x[mb][4 * g + 2], x[mb][4 * g + 3]));
+          fold(std::true_type{}, r);
+        } else {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+              r[mb][g] = __builtin_amdgcn_exp2f(x[mb][4 * g]) + __builtin_amdgcn_exp2f(x[mb][4 * g + 1]) +
+                         __builtin_amdgcn_exp2f(x[mb][4 * g + 2]) + __builtin_amdgcn_exp2f(x[mb][4 * g + 3]);
+          fold(std::false_type{}, r);
+        }
+      }
+      // staged in LDS ([16 query blocks][8 key blocks per tile x STAGE_TILES]) and written out in rows
+      if ((l32 & (SQ - 1)) == 0) {
+        const f32x4 wv = {w[0], w[1], w[2], w[3]};
+        *reinterpret_cast<f32x4*>(stage + ((wave * 4 + (l32 >> 3)) * (8 * STAGE_TILES) + (tt % STAGE_TILES) * 8 + hf * 4)) = wv;
       }
     }
-  }
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    l[qb] += __shfl_xor(l[qb], 32, 64);            // the two lane halves saw different keys
-    if (hf == 0) { part[wave][qb][l32][0] = m[qb]; part[wave][qb][l32][1] = l[qb]; }
-  }
-  __syncthreads();
-  float inv_l[QB], m_use[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    float mrow = -INFINITY, lrow = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) mrow = fmaxf(mrow, part[w][qb][l32][0]);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float mw = part[w][qb][l32][0];
-      if (mw != -INFINITY) lrow += part[w][qb][l32][1] * __builtin_amdgcn_exp2f(mw - mrow);
+  };
+  // rows of the staged scores -> S (key blocks [first_tile*8, +ntiles*8) of this workgroup's 16 query blocks)
+  auto flush = [&](int first_tt, int ntiles) __attribute__((always_inline)) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    asm volatile("s_barrier" ::: "memory");
+    const int ncol = ntiles * 8;
+    for (int x = tid; x < 16 * ncol; x += 256) {
+      const int qb = x / ncol, c = x % ncol;
+      const int qblk = rg * 16 + qb, j = (t_lo + first_tt) * 8 + c;
+      if (qblk < a.nq && j < a.nk) out[(int64_t)qblk * a.nk + j] = stage[qb * (8 * STAGE_TILES) + c];
     }
-    inv_l[qb] = lrow > 0.f ? 1.f / lrow : 0.f;
-    m_use[qb] = mrow == -INFINITY ? 0.f : mrow;
+    asm volatile("s_barrier" ::: "memory");
+  };
+
+  // Tile t has landed once at most the loads issued after its own are outstanding: those of tiles
+  // t+1 and t+2 (RI each).  (Sweep 2 writes S in batches, after a full wait, so stores never sit
+  // between the loads being counted.)
+  auto wait_tile = [&](int t) __attribute__((always_inline)) {
+    constexpr int G = RI;
+    if (SWEEP == 2 && t % STAGE_TILES < 3) __builtin_amdgcn_s_waitcnt(0x0F70);   // stores of the last write-out may be in flight
+    else if (t + 2 < nt) __builtin_amdgcn_s_waitcnt(((2 * G) & 15) | (((2 * G) >> 4) << 14) | 0x0F70);
+    else if (t + 1 < nt) __builtin_amdgcn_s_waitcnt((G & 15) | ((G >> 4) << 14) | 0x0F70);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+  auto one = [&](auto slot_tag, int t) __attribute__((always_inline)) {
+    wait_tile(t);
+    asm volatile("s_barrier" ::: "memory");      // everyone's part of tile t is in; slot of tile t-1 is free
+    if (t + NSLOT - 1 < nt) fire(t + NSLOT - 1);
+    tile_step(slot_tag, t);
+    if (SWEEP == 2 && ((t + 1) % STAGE_TILES == 0 || t + 1 == nt)) flush(t - t % STAGE_TILES, t % STAGE_TILES + 1);
+  };
+  for (int t = 0; t < nt; t += NSLOT) {
+    one(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < nt) one(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 < nt) one(std::integral_constant<int, 2>{}, t + 2);
+    if (t + 3 < nt) one(std::integral_constant<int, 3>{}, t + 3);
   }
 
-  // ---- sweep 2: normalised weights reduced to one score per (query block, key block)
-  float* out = S + (((int64_t)b * a.Hq + hq) * a.nq) * (int64_t)a.nk;
-  {
-    bf16x8 ka[KS], kb[KS];
-    auto emit = [&](const bf16x8 (&kf)[KS], int blk) __attribute__((always_inline)) {
-      float t[QB][16];
-      logits(kf, blk, t);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {              // key block blk*4 + g: 4 keys here, 4 in lane^32
-          float r;
-          if (a.est_pool == PSA_EST_MAX) {
-            r = fmaxf(fmaxf(t[qb][4 * g], t[qb][4 * g + 1]), fmaxf(t[qb][4 * g + 2], t[qb][4 * g + 3]));
-            r = fmaxf(r, __shfl_xor(r, 32, 64));
-            r = __builtin_amdgcn_exp2f(r - m_use[qb]) * inv_l[qb];
-#pragma unroll
-            for (int off = 1; off < SQ; off <<= 1) r = fmaxf(r, __shfl_xor(r, off, 64));
-          } else {
-            r = __builtin_amdgcn_exp2f(t[qb][4 * g] - m_use[qb]) + __builtin_amdgcn_exp2f(t[qb][4 * g + 1] - m_use[qb]) +
-                __builtin_amdgcn_exp2f(t[qb][4 * g + 2] - m_use[qb]) + __builtin_amdgcn_exp2f(t[qb][4 * g + 3] - m_use[qb]);
-            r += __shfl_xor(r, 32, 64);
-            r *= inv_l[qb];
-#pragma unroll
-            for (int off = 1; off < SQ; off <<= 1) r += __shfl_xor(r, off, 64);
-            r *= 1.f / (float)(SQ * SK);
-          }
-          const int j = blk * 4 + g;
-          if (hf == 0 && (l32 & (SQ - 1)) == 0 && qi[qb] < a.nq && j < a.nk) out[(int64_t)qi[qb] * a.nk + j] = r;
-        }
-    };
-    if (blk_lo < blk_hi) load_k(ka, blk_lo);
-    for (int blk = blk_lo; blk < blk_hi; blk += 2) {
-      if (blk + 1 < blk_hi) load_k(kb, blk + 1);
-      emit(ka, blk);
-      if (blk + 1 < blk_hi) {
-        if (blk + 2 < blk_hi) load_k(ka, blk + 2);
-        emit(kb, blk + 1);
-      }
-    }
+  if (SWEEP == 1) {
+    float p, q;
+    both_halves(l, p, q);                        // the two lane halves saw different keys
+    if (hf == 0 && row < nrows)
+      part[(((int64_t)b * a.Hq + hq) * nrows + row) * IMP_MAX_SPLIT + split] = make_float2(m, p + q);
   }
 }
 
 template <int D>
-static hipError_t launch_imp_mfma_t(const Plan& pl, const void* Qrep, const void* Krep, float* S, hipStream_t s) {
-  ImpMfmaArgs a;
+static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const void* Krep, float2* part, float* S,
+                                     hipStream_t s) {
+  ImpTileArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.mode = pl.rep_mode; a.causal = pl.causal; a.est_pool = pl.est_pool;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
-  dim3 grid((pl.nq * 8 + 63) / 64, pl.Hq, pl.B);
-  importance_mfma_kernel<D><<<grid, 256, 0, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), S, a);
+  const int row_groups = (pl.nq * 8 + 127) / 128;
+  const int ntile_all = (pl.nk * 8 + 63) / 64;
+  // enough workgroups for about three per compute unit
+  int ksplit = (768 + row_groups * pl.Hq * pl.B - 1) / (row_groups * pl.Hq * pl.B);
+  ksplit = ksplit < 1 ? 1 : (ksplit > IMP_MAX_SPLIT ? IMP_MAX_SPLIT : ksplit);
+  ksplit = ksplit > ntile_all ? ntile_all : ksplit;
+  a.ksplit = ksplit;
+  dim3 grid(row_groups, ksplit, pl.Hq * pl.B);
+  const int smem = 4 * 64 * D * 2 + 16 * 8 * 16 * (int)sizeof(float);   // ring of 4 tiles + staged scores
+  auto k1 = importance_tiles_kernel<D, 1>;
+  auto k2 = importance_tiles_kernel<D, 2>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (e != hipSuccess) return e;
+  k1<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  k2<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, a);
   return hipGetLastError();
 }
 
 bool importance_uses_mfma(const Plan& pl) { return pl.dtype == PSA_BF16 && pl.sq == 8 && pl.sk == 8; }
 
-hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, float* S, hipStream_t s) {
+hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, float* S, hipStream_t s) {
   if (importance_uses_mfma(pl))
-    return pl.d == 64 ? launch_imp_mfma_t<64>(pl, Qrep, Krep, S, s) : launch_imp_mfma_t<128>(pl, Qrep, Krep, S, s);
+    return pl.d == 64 ? launch_imp_tiles_t<64>(pl, Qrep, Krep, static_cast<float2*>(part), S, s)
+                      : launch_imp_tiles_t<128>(pl, Qrep, Krep, static_cast<float2*>(part), S, s);
   if (pl.dtype == PSA_F32)
     return pl.d == 64 ? launch_imp_t<float, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<float, 128>(pl, Qrep, Krep, S, s);
   return pl.d == 64 ? launch_imp_t<bf16_t, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<bf16_t, 128>(pl, Qrep, Krep, S, s);
