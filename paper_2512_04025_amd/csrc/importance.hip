@@ -556,13 +556,21 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   const int row_groups = (pl.nq * 8 + 127) / 128;
   const int ntile_all = (pl.nk * 8 + 63) / 64;
-  // enough workgroups for about three per compute unit
-  int ksplit = (768 + row_groups * pl.Hq * pl.B - 1) / (row_groups * pl.Hq * pl.B);
-  ksplit = ksplit < 1 ? 1 : (ksplit > IMP_MAX_SPLIT ? IMP_MAX_SPLIT : ksplit);
-  ksplit = ksplit > ntile_all ? ntile_all : ksplit;
+  // Key slices: the workgroups run in rounds of `slots` (what fits on the chip at once); pick the
+  // slice count with the least rounds x work-per-workgroup, preferring fewer slices on a tie.
+  const int smem = 4 * 64 * D * 2 + 16 * 8 * 16 * (int)sizeof(float);   // ring of 4 tiles + staged scores
+  const int per_cu = 160 * 1024 / smem < 3 ? 160 * 1024 / smem : 3;
+  const int slots = 256 * per_cu;
+  const int base = row_groups * pl.Hq * pl.B;
+  int ksplit = 1;
+  double best = 1e30;
+  for (int ks = 1; ks <= IMP_MAX_SPLIT && ks <= ntile_all; ++ks) {
+    const int tiles = (ntile_all + ks - 1) / ks;
+    const double cost = (double)((base * ks + slots - 1) / slots) * (tiles + 2.0);   // +2: start-up of a workgroup
+    if (cost < best - 1e-9) { best = cost; ksplit = ks; }
+  }
   a.ksplit = ksplit;
   dim3 grid(row_groups, ksplit, pl.Hq * pl.B);
-  const int smem = 4 * 64 * D * 2 + 16 * 8 * 16 * (int)sizeof(float);   // ring of 4 tiles + staged scores
   auto k1 = importance_tiles_kernel<D, 1>;
   auto k2 = importance_tiles_kernel<D, 2>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
