@@ -34,6 +34,10 @@ def _case(name):
         return si.small_variant(C["dit1p3b"], 1016, Hq=2, Hkv=2).with_(bq=64, bk=64), {}
     if name == "b32":             # (32, 32) blocks, 3 levels
         return si.small_variant(C["dit1p3b"], 1016, Hq=2, Hkv=2).with_(bq=32, bk=32, levels=3), {}
+    if name == "deep_d128":       # 5 levels on 32-token key blocks: pooled blocks of 2 rows, smaller than one load instruction
+        return si.small_variant(C["dit1p3b"], 1016, Hq=2, Hkv=2).with_(bq=64, bk=32, levels=5), {}
+    if name == "deep_d64":        # d = 64, 5 levels on 64-token key blocks: pooled blocks of 4 rows
+        return si.small_variant(C["stress"], 2000, Hq=2, Hkv=1, B=1).with_(bk=64), {}
     if name == "f32_d128":
         return si.small_variant(C["dit1p3b"], 520, Hq=2, Hkv=1).with_(dtype="f32"), {}
     raise KeyError(name)
@@ -231,12 +235,14 @@ def _attention_case(name, over, mask=None):
     ("stress_small", dict(budget=0.05)),
     ("b64", dict(budget=0.3)),
     ("b32", dict(budget=0.3)),
+    ("deep_d128", dict(budget=0.3)),
+    ("deep_d64", dict(budget=0.2)),
 ])
 def test_attention_matches_oracle_given_the_oracle_mask(name, over):
     _attention_case(name, over)
 
 
-@pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "stress_small", "tiny"])
+@pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "stress_small", "tiny", "deep_d128", "deep_d64"])
 def test_attention_random_masks(name):
     """Masks no allocation rule would produce: every level everywhere, empty levels, single blocks."""
     w, _ = _case(name)
