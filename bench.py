@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--heads", type=int, default=None, help="query-head count override (KV heads scale along)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-only microbenchmarks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--check-dense", action="store_true", help="also report rel-L2 of PSA vs dense attention")
     return ap.parse_args()
@@ -79,6 +80,33 @@ def measured_traffic(w, budget, kernel_prefix: str):
         if name.startswith(kernel_prefix):
             return v["read_bytes"] + v["write_bytes"]
     return None
+
+
+def attainable_peaks(torch, psa):
+    """What this GPU sustains on two trivial kernels of the library: a streaming copy (read + write
+    bytes per second) and a loop of nothing but bf16 32x32x16 MFMAs on register operands."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    psa.psa_probe_copy(src, dst, n)
+    e0.record()
+    for _ in range(5):
+        psa.psa_probe_copy(src, dst, n)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    psa.psa_probe_mfma(sink, 2048, 2000)
+    e0.record()
+    flops = 0.0
+    for _ in range(5):
+        flops += psa.psa_probe_mfma(sink, 2048, 2000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tflops = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"hbm_copy_gbs": copy_gbs, "mfma_bf16_tflops": mfma_tflops,
+            "note": "measured on this GPU by psa_probe_copy (1 GiB) and psa_probe_mfma (2048 workgroups x 2000 x 16 MFMAs per wavefront)"}
 
 
 def cpu_baseline(w, budget, Q, K, V, n_heads: int = 3):
@@ -211,6 +239,12 @@ def main():
             "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": measured_traffic(w, budget, "psa::pyramid_kernel"),
             "algorithmic_bytes": pyramid_bytes(w, w.levels)},
     }
+    if not args.no_attainable:
+        att = attainable_peaks(torch, psa)
+        out["attainable"] = att
+        out["roofline"]["frac_of_attainable"] = attn_tflops / att["mfma_bf16_tflops"]
+        if pyr_gbs is not None:
+            out["roofline_pyramid"]["frac_of_attainable"] = pyr_gbs / att["hbm_copy_gbs"]
     if w.dtype != "bf16":
         out["roofline"]["note"] += "; fp32 mode runs on the VALU (correctness mode), bf16 MFMA peak shown for scale only"
     if args.check_dense:

@@ -136,6 +136,20 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
 int psa_dense_ref(const psa_params* p, const void* Q, const void* K, const void* V, void* O,
                   float* lse, void* stream);
 
+/*
+ * Measurement aids (not part of the method; the benchmark uses them to state what this GPU sustains,
+ * next to the published peaks its roofline fractions are quoted against).
+ *
+ * psa_probe_copy: plain streaming copy of `bytes` (a multiple of 16) from src to dst, both device
+ *   pointers of at least that size; moves 2 * bytes through HBM.
+ * psa_probe_mfma: `workgroups` workgroups of 4 wavefronts, each wavefront issuing iters * 16
+ *   bfloat16 32x32x16 MFMAs on register operands.  sink: device, workgroups * 256 floats (written
+ *   once).  flops (host pointer, nullable) receives the floating-point operations of the launch.
+ * Both are asynchronous on `stream`; PSA_EINVAL for null pointers or sizes out of range.
+ */
+int psa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int psa_probe_mfma(float* sink, int workgroups, int iters, double* flops, void* stream);
+
 /* Static description of a status code (host pointer, never NULL). */
 const char* psa_status_str(int status);
 

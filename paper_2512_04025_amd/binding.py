@@ -64,10 +64,12 @@ def load_library() -> ctypes.CDLL:
     lib.psa_allocate_levels.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_dense_ref.argtypes = [pp, vp, vp, vp, vp, vp, vp]
+    lib.psa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    lib.psa_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
     for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd",
-                 "psa_dense_ref"):
+                 "psa_dense_ref", "psa_probe_copy", "psa_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -141,3 +143,16 @@ def psa_attention_fwd(p: PsaParams, Q, K, V, Kpyr, Vpyr, M, O, scratch, lse=None
 def psa_dense_ref(p: PsaParams, Q, K, V, O, lse=None, stream=None) -> None:
     _check(load_library().psa_dense_ref(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(lse),
                                         _stream(stream)), "psa_dense_ref")
+
+
+def psa_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(load_library().psa_probe_copy(_ptr(src), _ptr(dst), ctypes.c_size_t(nbytes), _stream(stream)),
+           "psa_probe_copy")
+
+
+def psa_probe_mfma(sink, workgroups: int, iters: int, stream=None) -> float:
+    """Launches the MFMA-only loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().psa_probe_mfma(_ptr(sink), ctypes.c_int(workgroups), ctypes.c_int(iters),
+                                         ctypes.byref(flops), _stream(stream)), "psa_probe_mfma")
+    return flops.value

@@ -1,0 +1,57 @@
+// Two measurement aids: what this GPU actually sustains for a plain streaming copy and for a loop of
+// nothing but bfloat16 MFMAs.  The benchmark reports the kernels of the method against the published
+// peaks AND against these attainable figures (the shader clock under load is well below the one
+// behind the published matrix peak).  Not part of the method.
+#include "psa_dev.h"
+#include "psa_internal.h"
+
+namespace psa {
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                         size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Every wavefront issues iters x 16 independent-enough 32x32x16 MFMAs (4 accumulators); operands are
+// registers, there is no memory traffic besides one store per lane at the end.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters) {
+  const int lane = threadIdx.x & 63;
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)((lane + e) & 3);
+    b[e] = (__bf16)(1.0f / 64.0f);
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[j][v];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}  // namespace psa
+
+extern "C" int psa_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || bytes == 0 || bytes % 16) return PSA_EINVAL;
+  psa::probe_copy_kernel<<<256 * 16, 256, 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const psa::u32x4*>(src), static_cast<psa::u32x4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
+extern "C" int psa_probe_mfma(float* sink, int workgroups, int iters, double* flops, void* stream) {
+  if (!sink || workgroups <= 0 || iters <= 0) return PSA_EINVAL;
+  psa::probe_mfma_kernel<<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(sink, iters);
+  if (flops) *flops = (double)workgroups * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+  return hipGetLastError() == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
