@@ -278,6 +278,23 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
   const int t_lo = split * per;
   int nt = (t_lo + per < ntile_all ? t_lo + per : ntile_all) - t_lo;
   nt = nt > 0 ? nt : 0;
+  const int nt_slice = nt;                       // tiles of the slice, visible or not
+  // Causal: positions grow with the representative index on both sides, so the workgroup's rows see
+  // ALL keys of a tile whose last key lies at or before its first row, and NONE of a tile whose first
+  // key lies after its last valid row.  Tiles of the second kind end the slice early (their scores
+  // are zero); tiles of the first kind take the unmasked path.
+  const int row_first = rg * 128;
+  int row_last = rg * 128 + 127;
+  row_last = row_last < nrows ? row_last : nrows - 1;
+  const int qpos_min = rep_pos(a.mode, row_first / SQ, row_first % SQ, a.bq, SQ, a.N);
+  const int qpos_max = rep_pos(a.mode, row_last / SQ, row_last % SQ, a.bq, SQ, a.N);
+  auto key_pos = [&](int c) __attribute__((always_inline)) {   // position of representative key c (clamped to the last)
+    c = c < nkeys ? c : nkeys - 1;
+    return rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N);
+  };
+  if (a.causal) {
+    while (nt > 0 && key_pos((t_lo + nt - 1) * BN) > qpos_max) --nt;
+  }
 
   {  // ring starts as zeros: a lane whose key row is out of range leaves its LDS slot alone
     const u32x4 z = {0u, 0u, 0u, 0u};
@@ -316,8 +333,8 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
   const bool rows_full = rg * 128 + 128 <= nrows;
   const int gk = a.bk / SK;
   auto is_plain = [&](int tile) __attribute__((always_inline)) {   // all 64 keys and all rows valid, nothing hidden
-    return rows_full && !a.causal && (a.mode == PSA_REP_STRIDED ? tile * BN + BN <= nkeys
-                                                                : (int64_t)(tile * BN + BN - 1) * gk < a.N);
+    const bool keys_full = a.mode == PSA_REP_STRIDED ? tile * BN + BN <= nkeys : (int64_t)(tile * BN + BN - 1) * gk < a.N;
+    return rows_full && keys_full && (!a.causal || key_pos(tile * BN + BN - 1) <= qpos_min);
   };
   auto both_halves = [&](float x, float& p, float& q) __attribute__((always_inline)) {
     const uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -539,6 +556,13 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
     if (t + 3 < nt) one(std::integral_constant<int, 3>{}, t + 3);
   }
 
+  if (SWEEP == 2 && nt < nt_slice) {           // key blocks of the slice that no row of this workgroup sees: score 0
+    const int j0 = (t_lo + nt) * 8, ncol = (nt_slice - nt) * 8;
+    for (int x = tid; x < 16 * ncol; x += 256) {
+      const int qblk = rg * 16 + x / ncol, j = j0 + x % ncol;
+      if (qblk < a.nq && j < a.nk) out[(int64_t)qblk * a.nk + j] = 0.f;
+    }
+  }
   if (SWEEP == 1) {
     float p, q;
     both_halves(l, p, q);                        // the two lane halves saw different keys
