@@ -165,6 +165,9 @@ def main():
     from paper_2512_04025_amd.plumbing import Buffers, from_dev, to_dev
 
     w = si.CONFIGS[args.workload]
+    # the importance estimator of the workload (8 pooled representatives per block) stays the same when
+    # the pyramid depth is overridden, so --levels 1 is block-sparse attention on the SAME scores
+    sq, sk = 8, w.bk >> (w.levels - 1)
     if args.levels:
         w = w.with_(levels=args.levels)
     if args.seq or args.heads:
@@ -173,7 +176,7 @@ def main():
     budget = args.budget if args.budget is not None else w.budget
     gp = psa.make_params(w.B, w.Hq, w.Hkv, w.N, w.d, w.bq, w.bk, w.levels,
                          dtype=psa.PSA_BF16 if w.dtype == "bf16" else psa.PSA_F32, causal=w.causal,
-                         rep_mode=psa.PSA_REP_POOLED, est_pool=psa.PSA_EST_MAX,
+                         sq=sq, sk=sk, rep_mode=psa.PSA_REP_POOLED, est_pool=psa.PSA_EST_MAX,
                          alloc_mode=psa.PSA_ALLOC_BUDGET, budget=budget)
     torch.cuda.set_device(0)
     Q, K, V = si.generate_qkv(w)

@@ -72,7 +72,7 @@ struct LevelState {
 // D: head dimension; NW: wavefronts per workgroup (each owns 32 query rows); SC: every level's pooled
 // block holds at least as many rows as one load instruction covers
 template <int D, int NW, bool SC>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
 void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                       const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
                       const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
