@@ -92,19 +92,36 @@ __global__ __launch_bounds__(256) void alloc_kernel(const float* __restrict__ S,
   __syncthreads();
   const int n_vis = nvis_s;
 
-  // bitonic sort, ascending
+  // bitonic sort, ascending.  Each wavefront owns a contiguous quarter of the keys: a stage whose
+  // partner distance stays inside a quarter touches only the wavefront's own keys, and since the LDS
+  // serves one wavefront's operations in order such stages need no workgroup barrier (only a fence
+  // that keeps the compiler from moving LDS operations across).  Only the few stages with a longer
+  // distance synchronise the workgroup.
+  const int chunk = a.P >> 2;                   // keys per wavefront (P >= 256: at least 64)
+  auto exchange = [&](int t, int jj, int k) {       // jj is a power of two
+    const int lo = ((t & ~(jj - 1)) << 1) + (t & (jj - 1));
+    const int hi = lo + jj;
+    const uint64_t x = keys[lo], y = keys[hi];
+    const bool up = (lo & k) == 0;
+    if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+  };
+  bool local_before = false;
   for (int k = 2; k <= a.P; k <<= 1) {
     for (int jj = k >> 1; jj > 0; jj >>= 1) {
-      for (int t = tid; t < (a.P >> 1); t += 256) {
-        const int lo = ((t / jj) * (jj << 1)) + (t % jj);
-        const int hi = lo + jj;
-        const uint64_t x = keys[lo], y = keys[hi];
-        const bool up = (lo & k) == 0;
-        if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+      if (a.P >= 256 && jj < chunk) {
+        for (int t = wave * (chunk >> 1) + lane; t < (wave + 1) * (chunk >> 1); t += 64) exchange(t, jj, k);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        local_before = true;
+      } else {
+        if (local_before) __syncthreads();
+        for (int t = tid; t < (a.P >> 1); t += 256) exchange(t, jj, k);
+        __syncthreads();
+        local_before = false;
       }
-      __syncthreads();
     }
   }
+  if (local_before) __syncthreads();
 
   const int C = a.P >= 256 ? a.P / 256 : 1;   // sorted elements per thread (contiguous)
   const int k0 = tid * C;
