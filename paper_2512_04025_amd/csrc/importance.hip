@@ -1,6 +1,8 @@
 // Block importance estimation (Sec. 3.3.1, Eq. 4 and the mean variant of App. B.2).
 //
-// Two kernels:
+// Three kernels:
+//   importance_tiles_kernel  the matrix-core version for bfloat16 with 8 representatives per block
+//                      (described where it is defined); the two below serve every other case
 //   reps_kernel        gathers the representative tokens of every block (the "sampled" tokens of
 //                      Eq. 4): either one token per stride or the mean of a contiguous group.
 //   importance_kernel  one workgroup per query block: logits of its s_q representative queries
