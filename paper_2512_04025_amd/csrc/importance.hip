@@ -289,7 +289,8 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
   int row_last = rg * 128 + 127;
   row_last = row_last < nrows ? row_last : nrows - 1;
   const int qpos_min = rep_pos(a.mode, row_first / SQ, row_first % SQ, a.bq, SQ, a.N);
-  const int qpos_max = rep_pos(a.mode, row_last / SQ, row_last % SQ, a.bq, SQ, a.N);
+  int qpos_max = rep_pos(a.mode, row_last / SQ, row_last % SQ, a.bq, SQ, a.N);
+  if (qpos_max < 0) qpos_max = a.N - 1;          // last rows cover no token: the last valid one ends at N - 1
   auto key_pos = [&](int c) __attribute__((always_inline)) {   // position of representative key c (clamped to the last)
     c = c < nkeys ? c : nkeys - 1;
     return rep_pos(a.mode, c / SK, c % SK, a.bk, SK, a.N);

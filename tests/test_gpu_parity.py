@@ -38,6 +38,16 @@ def _case(name):
         return si.small_variant(C["dit1p3b"], 1016, Hq=2, Hkv=2).with_(bq=64, bk=32, levels=5), {}
     if name == "deep_d64":        # d = 64, 5 levels on 64-token key blocks: pooled blocks of 4 rows
         return si.small_variant(C["stress"], 2000, Hq=2, Hkv=1, B=1).with_(bk=64), {}
+    if name.startswith("edge_"):  # degenerate shapes: a single (partial) block, one level, tiny N, odd block sizes
+        base = si.small_variant(C["dit1p3b"], 1016, Hq=2, Hkv=1)
+        return {
+            "edge_one_partial_block": base.with_(N=100, grid=(1, 10, 10), bq=128, bk=128, levels=4),
+            "edge_n8": base.with_(N=8, grid=(1, 2, 4), bq=32, bk=32, levels=3),
+            "edge_single_level": base.with_(N=520, grid=(1, 20, 26), bq=64, bk=64, levels=1),
+            "edge_causal_tiny": base.with_(N=130, grid=(1, 10, 13), bq=128, bk=64, levels=4, causal=True),
+            "edge_bq96": base.with_(N=700, grid=(1, 20, 35), bq=96, bk=64, levels=3),     # rows kernel fallback
+            "edge_eight_levels": base.with_(N=2048, grid=(2, 32, 32), bq=128, bk=128, levels=8),
+        }[name], {}
     if name == "f32_d128":
         return si.small_variant(C["dit1p3b"], 520, Hq=2, Hkv=1).with_(dtype="f32"), {}
     raise KeyError(name)
@@ -240,6 +250,22 @@ def _attention_case(name, over, mask=None):
 ])
 def test_attention_matches_oracle_given_the_oracle_mask(name, over):
     _attention_case(name, over)
+
+
+@pytest.mark.parametrize("name", ["edge_one_partial_block", "edge_n8", "edge_single_level", "edge_causal_tiny",
+                                  "edge_bq96", "edge_eight_levels"])
+def test_degenerate_shapes_whole_path(name):
+    """Shapes at the edges of what the entry points accept: allocation from the oracle's scores, then
+    attention with that mask, both against the oracle."""
+    import torch
+    r = Run(name, budget=0.5)
+    S = orc.importance(r.Q64, r.K64, r.op)
+    M = orc.allocate_levels(S, r.op)
+    psa.psa_build_pyramid(r.gp, r.Kd, r.Vd, r.buf.Kpyr, r.buf.Vpyr)
+    psa.psa_allocate_levels(r.gp, r.Qd, r.Kd, r.buf.Kpyr, r.buf.M, r.buf.scratch, scores_out=r.buf.S)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(r.buf.S.cpu().numpy(), S, rtol=2e-3, atol=1e-6)
+    _attention_case(name, dict(budget=0.5), mask=M)
 
 
 @pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "stress_small", "tiny", "deep_d128", "deep_d64"])
