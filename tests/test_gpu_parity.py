@@ -122,7 +122,9 @@ def test_dense_ref_matches_oracle(name):
     ("tiny", dict(rep_mode="strided", sq=64, sk=64)),          # every token: exact block max of softmax
     ("dit_small", {}),
     ("dit_odd", dict(est_pool="mean")),
+    ("dit_small", dict(rep_mode="strided", est_pool="mean")),
     ("vlm_small", {}),
+    ("vlm_small", dict(est_pool="mean")),
     ("vlm_ragged", dict(rep_mode="strided")),
     ("stress_small", {}),
     ("b32", dict(sq=4, sk=16, rep_mode="strided")),
