@@ -45,7 +45,9 @@ struct MfmaArgs {
   int64_t lvl_off[PSA_MAX_LEVELS + 2];
 };
 
-constexpr int BN = 64;     // key columns per tile
+#ifndef PSA_ATTN_TILE
+#define PSA_ATTN_TILE 64
+#endif
 constexpr float LAZY_RESCALE = 8.0f;
 // word 3 of a raw (untyped, stride 0) buffer descriptor on gfx9-family targets: 32-bit data format
 constexpr int RSRC_FLAGS = 0x00020000;
@@ -71,8 +73,9 @@ struct LevelState {
 
 // D: head dimension; NW: wavefronts per workgroup (each owns 32 query rows); SC: every level's pooled
 // block holds at least as many rows as one load instruction covers
-template <int D, int NW, bool SC>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, D == 64 ? 3 : 2)))
+// BN: key columns per tile (64, or 32: fewer registers, three wavefronts per SIMD)
+template <int D, int NW, bool SC, int BN>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(BN == 32 ? 3 : 2, (D == 64 || BN == 32) ? 3 : 2)))
 void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                       const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
                       const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
@@ -86,11 +89,15 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   constexpr int RP256 = 16 / CPR;            // rows per 256 bytes of LDS
   constexpr int ROWB = D * 2;                // bytes per row
   constexpr int TILEB = BN * ROWB;           // bytes per tile (a power of two)
-  constexpr int NA = 2 * (D / 16);           // MFMAs of S^T = K Q^T per tile
-  constexpr int NB = 4 * (D / 32);           // MFMAs of O^T += V^T P^T per tile
-  constexpr int MPC = 16 / NB;               // 3-input maxima handled next to one MFMA of the second product
+  constexpr int HALVES = BN / 32;            // 32-column halves of a tile (one accumulator tuple each)
+  constexpr int LG_BN = BN == 64 ? 6 : 5;
+  constexpr int NPAIR = HALVES * 8;          // pairs of probabilities per lane and tile
+  constexpr int NA = HALVES * (D / 16);      // MFMAs of S^T = K Q^T per tile
+  constexpr int NB = (BN / 16) * (D / 32);   // MFMAs of O^T += V^T P^T per tile
+  constexpr int MPC = NPAIR / NB;            // 3-input maxima handled next to one MFMA of the second product
+  static_assert(BN == 64 || BN == 32, "tile width");
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-  static_assert(MPC * NB == 16, "chunking of the softmax work");
+  static_assert(MPC * NB == NPAIR, "chunking of the softmax work");
   // LDS map: K[2] | V[2] | per-wavefront table for irregular tiles | block list
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   constexpr int OFF_K = 0, OFF_V = 2 * TILEB, OFF_FIX = 4 * TILEB, OFF_LIST = OFF_FIX + NW * 512;
@@ -128,7 +135,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const int nb = my_cnt[h - 1];
     const int lg_th = a.lg_bk - (h - 1);
     total_blocks += nb;
-    total_tiles += ((nb << lg_th) + BN - 1) >> 6;
+    total_tiles += ((nb << lg_th) + BN - 1) >> LG_BN;
   }
   for (int x = tid; x < total_blocks; x += NT) list[x] = my_idx[x];
   {  // tile buffers start as zeros: a lane whose source row is out of range leaves its LDS slot alone
@@ -146,7 +153,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
     ls.lg_th = a.lg_bk - (h - 1);
     ls.nblk = my_cnt[h - 1];
-    ls.ntl = ((ls.nblk << ls.lg_th) + BN - 1) >> 6;
+    ls.ntl = ((ls.nblk << ls.lg_th) + BN - 1) >> LG_BN;
     int lim = a.N >> (h - 1);                                  // rows below cover 2^(h-1) valid tokens
     if (a.causal) {
       const int vis = (row0 + 1) >> (h - 1);                   // rows below end at or before row0
@@ -207,9 +214,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   int plan_jl = 0;                            // block id of tile row `lane`
   uint32_t plan_off = 0;                      // byte offset of the source row of tile row `lane`
   auto plan_read = [&]() __attribute__((always_inline)) {
-    const int g0 = ld_tl << 6;
+    const int g0 = ld_tl << LG_BN;
     {
-      const int e = (g0 + lane) >> ls.lg_th;
+      const int e = (g0 + (lane & (BN - 1))) >> ls.lg_th;
       plan_jl = (int)list[ls.lvl_start + (e < ls.nblk ? e : ls.nblk - 1)];
     }
     if (!SC) {
@@ -223,7 +230,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   auto plan_resolve = [&]() __attribute__((always_inline)) {
     // the whole tile, one row per lane: its source row, and whether any row is past the kept blocks,
     // the ragged tail or the causal limit
-    const int g = (ld_tl << 6) + lane, e = g >> ls.lg_th;
+    const int g = (ld_tl << LG_BN) + (lane & (BN - 1)), e = g >> ls.lg_th;
     const int prow = (plan_jl << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));
     plan_irregular = (e >= ls.nblk) | (prow >= ls.lim);
     plan_off = (uint32_t)prow * (uint32_t)ROWB;
@@ -232,7 +239,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     if (SC) {    // the first row of the load decides (the others follow it inside the same block): one lane read
       planK[k] = (uint32_t)__builtin_amdgcn_readlane((int)plan_off, (k * NW + wave) * RPI);
     } else {
-      const int g = (ld_tl << 6) + (k * NW + wave) * RPI + lrow;   // position in the level's token stream
+      const int g = (ld_tl << LG_BN) + (k * NW + wave) * RPI + lrow;   // position in the level's token stream
       const int prow = (plan_jj[k] << ls.lg_th) | (g & ((1 << ls.lg_th) - 1));   // row in the level-h array
       planK[k] = (uint32_t)(prow - lrow) * (uint32_t)ROWB;       // (the lane's own row offset is in klane / vlane)
     }
@@ -298,7 +305,6 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 
   f32x16 oacc[D / 32];
   float m_run = -INFINITY, l_run = 0.f;
-  float l_part = 0.f;                         // second partial row sum; folded into l_run at the end
 #pragma unroll
   for (int md = 0; md < D / 32; ++md)
 #pragma unroll
@@ -322,7 +328,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // MFMA number j of the first product: key half j & 1, k-step j >> 1 (neighbours in issue order are
   // independent); of the second product: channel block j % (D/32), k-step j / (D/32)
   auto read_k = [&](int j, uint32_t flip) __attribute__((always_inline)) {   // compiler-managed (prologue only)
-    const int mb = j & 1, ks = j >> 1;
+    const int mb = j % HALVES, ks = j / HALVES;
     return *reinterpret_cast<const bf16x8*>(smem + (kaddr0 ^ flip ^ (uint32_t)(ks << 5)) + mb * 32 * ROWB);
   };
   // In the steady state every read of a K / V tile is written as assembly with its own counter
@@ -335,8 +341,14 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) kaddr[ks] = kaddr0 ^ (uint32_t)(ks << 5);
   auto read_k_asm = [&](bf16x8& dst, int j, int flip) __attribute__((always_inline)) {
-    const int mb = j & 1, ks = j >> 1;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(kaddr[ks]), "n"(flip + mb * 32 * ROWB));
+    const int mb = j % HALVES, ks = j / HALVES;
+    if (BN == 32) {   // three wavefronts per SIMD leave no room for one address register per k-step
+      uint32_t ad;
+      asm volatile("v_xor_b32 %0, %1, %2" : "=v"(ad) : "n"(ks << 5), "v"(kaddr0));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(ad), "n"(flip + mb * 32 * ROWB));
+    } else {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(kaddr[ks]), "n"(flip + mb * 32 * ROWB));
+    }
   };
   auto take_k = [&](bf16x8& frag, int later) __attribute__((always_inline)) {
     asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(later));
@@ -360,12 +372,12 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // one of the 64 key columns (additive term, last covered token) into a table private to the
   // wavefront; then every lane reads the terms of the columns its registers hold:
   // register v of half mb is key column mb*32 + (v/4)*8 + hf*4 + v%4 of the tile.
-  auto fixup_special = [&](f32x16 (&sc)[2], int t) __attribute__((always_inline)) {
+  auto fixup_special = [&](f32x16 (&sc)[HALVES], int t) __attribute__((always_inline)) {
     int h = 1, start = 0, tl = t, nb = 0, lg_th = a.lg_bk;
     for (;; ++h) {
       nb = my_cnt[h - 1];
       lg_th = a.lg_bk - (h - 1);
-      const int ntl = ((nb << lg_th) + BN - 1) >> 6;
+      const int ntl = ((nb << lg_th) + BN - 1) >> LG_BN;
       if (tl < ntl || h == a.H) break;
       tl -= ntl;
       start += nb;
@@ -375,18 +387,18 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     float* term = reinterpret_cast<float*>(smem + OFF_FIX + wave * 512);
     int* last = reinterpret_cast<int*>(smem + OFF_FIX + wave * 512 + 256);
     {
-      const int g = (tl << 6) + lane, e = g >> lg_th;
+      const int g = (tl << LG_BN) + (lane & (BN - 1)), e = g >> lg_th;
       const int jj = (int)list[start + (e < nb ? e : nb - 1)];
       const int pr = (jj << lg_th) | (g & ((1 << lg_th) - 1));       // row in the level-h array
       const int first = pr << hm1;
       int c = a.N - first;
       c = c < 0 ? 0 : (c > span ? span : c);
       if (e >= nb) c = 0;
-      term[lane] = c == 0 ? -INFINITY : (__log2f((float)c) - (float)hm1) / a.scale_log2;
-      last[lane] = first + c - 1;
+      term[lane & (BN - 1)] = c == 0 ? -INFINITY : (__log2f((float)c) - (float)hm1) / a.scale_log2;
+      last[lane & (BN - 1)] = first + c - 1;
     }
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < HALVES; ++mb)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         const int col = mb * 32 + g4 * 8 + hf * 4;
@@ -429,7 +441,6 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       const float m_new = fmaxf(m_run, tmax);
       const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
       l_run *= alpha;
-      l_part *= alpha;
 #pragma unroll
       for (int md = 0; md < D / 32; ++md)
 #pragma unroll
@@ -440,19 +451,18 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   };
 
   // One pair of probabilities of the current tile: p = 2^(scale*s + shift) -> bfloat16 P^T registers
-  // and the two partial row sums.  Pair q holds tile columns of registers 2q, 2q+1 (16 pairs per tile).
-  auto exp_pair = [&](const f32x16 (&sc)[2], bf16x8 (&pf)[4], float shift, int q) __attribute__((always_inline)) {
+  // and the row sum.  Pair q holds tile columns of registers 2q, 2q+1.
+  auto exp_pair = [&](const f32x16 (&sc)[HALVES], bf16x8 (&pf)[BN / 16], float shift, int q) __attribute__((always_inline)) {
     const int e = 2 * q, mb = e >> 4, v = e & 15;
     const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
     const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v + 1], a.scale_log2, shift));
-    l_run += p0;
-    l_part += p1;
+    l_run += p0 + p1;
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
     {  // keep the arithmetic in this slice: pure values are otherwise free to sink to their first use
       uint32_t bits = __builtin_bit_cast(uint32_t, pk);
-      asm volatile("" : "+v"(bits), "+v"(l_run), "+v"(l_part));
+      asm volatile("" : "+v"(bits), "+v"(l_run));
       pk = __builtin_bit_cast(bf16x2, bits);
     }
     pf[2 * mb + (v >> 3)][v & 7] = pk[0];
@@ -462,8 +472,12 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // BOTH products: about one probability per MFMA.  Pairs 0..NPA-1 of tile t are computed beside the
   // first product of tile t+1; the rest beside the second product of tile t, each just before the
   // k-step that consumes it (k-step ks of the second product reads pairs 4ks..4ks+3).
-  constexpr int NPA = 10;
-  constexpr int BSTRIDE = NB / 8;             // slots of the second product per late pair
+  constexpr int NPA = BN == 64 ? 10 : (D == 128 ? 5 : 6);
+  constexpr int BSTRIDE = BN == 64 ? NB / 8 : 1;   // slots of the second product per late pair
+  // every late pair is ready before the first MFMA that reads its P^T fragment (pairs 4f..4f+3 make fragment f)
+  static_assert((NPAIR - NPA - 1) * BSTRIDE < (D / 32) * ((NPAIR - 1) / 4) && NPA % 4 != 0 &&
+                    ((NPA / 4 + 1) * 4 - NPA - 1) * BSTRIDE < (D / 32) * (NPA / 4),
+                "late probabilities must precede their consumers");
 
   // One step per tile t (MORE: a tile t+1 exists):
   //   wait + barrier | fire V(t+1), K(t+2)
@@ -476,7 +490,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // Tiles past the end of the row are planned and requested like any other (null tiles: their loads
   // are all out of range and fetch nothing) and the scores of the first of them are computed and
   // dropped, so the step has one shape and no conditions besides the two rare paths.
-  auto step = [&](auto parity_tag, f32x16 (&sc)[2], f32x16 (&sn)[2], int t) __attribute__((always_inline)) {
+  auto step = [&](auto parity_tag, f32x16 (&sc)[HALVES], f32x16 (&sn)[HALVES], int t) __attribute__((always_inline)) {
     constexpr int PAR = decltype(parity_tag)::value;      // t & 1, known at each call site
     constexpr bool MORE = true, k3 = true, k4 = true;
     const bool has_next = t + 1 < total_tiles;
@@ -485,7 +499,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     fire_v(t + 1);
     constexpr uint32_t flip_n = PAR ? 0u : (uint32_t)TILEB;
     constexpr uint32_t flip_c = PAR ? (uint32_t)TILEB : 0u;
-    bf16x8 pf[4];
+    bf16x8 pf[BN / 16];
     bf16x8 fr[4];                             // rolling operand fragments, requested PF MFMAs ahead
     constexpr int PF = 2;
     __builtin_amdgcn_sched_barrier(0);
@@ -497,7 +511,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     for (int j = 0; j < NA; ++j) {
       if (MORE) {
         if (j + PF < NA) read_k_asm(fr[(j + PF) & 3], j + PF, (int)flip_n);
-        const int mb = j & 1, ks = j >> 1;
+        const int mb = j % HALVES, ks = j / HALVES;
         take_k(fr[j & 3], (j + PF < NA ? j + PF : NA - 1) - j);
         sn[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], qf[ks], ks == 0 ? zero16 : sn[mb], 0, 0, 0);
       }
@@ -523,7 +537,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       const int md = j % (D / 32), ks = j / (D / 32);
       const bf16x8 vfrag = take_vt(vlo[j & 3], vhi[j & 3], 2 * ((j + PF < NB ? j + PF : NB - 1) - j));
       oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[ks], oacc[md], 0, 0, 0);
-      if (j % BSTRIDE == 0 && NPA + j / BSTRIDE < 16) exp_pair(sc, pf, shift_cur, NPA + j / BSTRIDE);
+      if (j % BSTRIDE == 0 && NPA + j / BSTRIDE < NPAIR) exp_pair(sc, pf, shift_cur, NPA + j / BSTRIDE);
       if (k4) {
 #pragma unroll
         for (int k = j; k < RI; k += NB) plan_part(k);
@@ -542,9 +556,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     if (has_next) shift_cur = advance_max(rawmax, t + 1);
   };
 
-  f32x16 sA[2], sB[2];
+  f32x16 sA[HALVES], sB[HALVES];
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+  for (int mb = 0; mb < HALVES; ++mb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { sA[mb][v] = 0.f; sB[mb][v] = 0.f; }
   __syncthreads();                           // block list is in LDS
@@ -577,13 +591,13 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     wg_barrier();
 #pragma unroll
     for (int j = 0; j < NA; ++j) {
-      const int mb = j & 1, ks = j >> 1;
+      const int mb = j % HALVES, ks = j / HALVES;
       sA[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(j, 0u), qf[ks], ks == 0 ? zero16 : sA[mb], 0, 0, 0);
     }
     if (spec_ring & 1u) fixup_special(sA, 0);
     float rawmax = -INFINITY;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < HALVES; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) rawmax = fmaxf(rawmax, sA[mb][v]);
     shift_cur = advance_max(rawmax, 0);
@@ -607,9 +621,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // ---- epilogue: O = o / l ; lane (row, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
   {
     float l_lo, l_hi;
-    l_run += l_part;
     both_halves(l_run, l_lo, l_hi);
-    const float l_tot = l_lo + l_hi;   // (l_run already holds both partial sums)
+    const float l_tot = l_lo + l_hi;
     if (qrow < row_end) {
       const float inv = 1.f / l_tot;
       bf16_t* op = O + (qhead * a.N + qrow) * D;
@@ -627,11 +640,11 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   }
 }
 
-size_t attn_mfma_smem_bytes(int d, int nk) {
-  return 4 * (size_t)BN * d * sizeof(bf16_t) + 4 * 512 + (((size_t)nk * 2 + 15) & ~(size_t)15);
+size_t attn_mfma_smem_bytes(int d, int nk, int bn) {
+  return 4 * (size_t)bn * d * sizeof(bf16_t) + 4 * 512 + (((size_t)nk * 2 + 15) & ~(size_t)15);
 }
 
-template <int D, int NW, bool SC>
+template <int D, int NW, bool SC, int BN>
 static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                                 const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                                 hipStream_t s) {
@@ -645,8 +658,8 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.items = pl.B * pl.Hq * pl.nq * a.slices;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
-  const size_t smem = attn_mfma_smem_bytes(D, pl.nk);
-  auto kern = attn_mfma_kernel<D, NW, SC>;
+  const size_t smem = attn_mfma_smem_bytes(D, pl.nk, BN);
+  auto kern = attn_mfma_kernel<D, NW, SC, BN>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)smem);
   if (e != hipSuccess) return e;
@@ -662,8 +675,9 @@ static hipError_t launch_mfma_d(const Plan& pl, const void* Q, const void* K, co
                                 hipStream_t s) {
   constexpr int RPI = 64 / (D / 8);           // tile rows per wave-wide 16 B/lane load
   const bool blocks_cover_a_load = (pl.bk >> (pl.H - 1)) >= RPI;
-  return blocks_cover_a_load ? launch_mfma_t<D, NW, true>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s)
-                             : launch_mfma_t<D, NW, false>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+  constexpr int BN = PSA_ATTN_TILE;
+  return blocks_cover_a_load ? launch_mfma_t<D, NW, true, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s)
+                             : launch_mfma_t<D, NW, false, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
 }
 
 hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
