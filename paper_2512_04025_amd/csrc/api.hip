@@ -62,6 +62,11 @@ int make_plan(const psa_params* p, Plan* o) {
   o->off_krep = s;   s += o->krep_is_pyramid ? 0 : align256((size_t)o->B * o->Hkv * o->nk * o->sk * o->d * o->esize);
   o->off_scores = s; s += align256(rows_q * o->nk * sizeof(float));
   o->off_part = s;   s += align256(heads_q * o->nq * o->sq * 8 * 2 * sizeof(float));   // up to 8 key slices x (max, sum)
+  {  // block maxima of the matrix-core importance path with max pooling: [heads][rows padded to 128][key blocks padded to 8]
+    const bool used = o->dtype == PSA_BF16 && o->sq == 8 && o->sk == 8 && o->est_pool == PSA_EST_MAX;
+    const size_t rows_pad = (((size_t)o->nq * 8 + 127) / 128) * 128, cols_pad = (((size_t)o->nk * 8 + 63) / 64) * 8;
+    o->off_bmax = s;   s += used ? align256(heads_q * rows_pad * cols_pad * sizeof(float)) : 0;
+  }
   o->off_rowcnt = s; s += align256(rows_q * ROWCNT_STRIDE * sizeof(uint32_t));
   o->off_idx = s;    s += align256(rows_q * o->nk * sizeof(uint16_t));
   o->off_cnt = s;    s += align256(rows_q * CNT_STRIDE * sizeof(int32_t));
@@ -163,7 +168,7 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
       krep = kr;
     }
     float* sdst = scores_out ? scores_out : reinterpret_cast<float*>(at(scratch, pl.off_scores));
-    if (launch_importance(pl, qrep, krep, at(scratch, pl.off_part), sdst, s) != hipSuccess) return PSA_ELAUNCH;
+    if (launch_importance(pl, qrep, krep, at(scratch, pl.off_part), at(scratch, pl.off_bmax), sdst, s) != hipSuccess) return PSA_ELAUNCH;
     scores = sdst;
   } else if (scores_out && scores_out != scores_in) {
     const size_t bytes = (size_t)pl.B * pl.Hq * pl.nq * pl.nk * sizeof(float);

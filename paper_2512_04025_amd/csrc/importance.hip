@@ -236,6 +236,7 @@ constexpr int IMP_MAX_SPLIT = 8;
 
 struct ImpTileArgs {
   int N, Hq, Hkv, nq, nk, bq, bk, mode, causal, est_pool, ksplit;
+  int bm_rows, bm_pitch;     // padded rows per head and floats per row of the block-maxima buffer
   float scale_log2;
 };
 
@@ -245,7 +246,7 @@ template <int D, int SWEEP>
 __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
                                                                const bf16_t* __restrict__ Krep,
                                                                float2* __restrict__ part, float* __restrict__ S,
-                                                               ImpTileArgs a) {
+                                                               float* __restrict__ bmax, ImpTileArgs a) {
   constexpr int SQ = 8, SK = 8, KS = D / 16, BN = 64, NW = 4, NSLOT = 4;
   constexpr int CPR = D / 8, RPI = 64 / CPR, NINST = BN / RPI, RI = NINST / NW, RP256 = 16 / CPR;
   constexpr int ROWB = D * 2, TILEB = BN * ROWB;
@@ -459,6 +460,29 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
           m = mn;
         }
       }
+      if (bmax) {
+        // Max pooling needs only the largest logit of every (row, key block): keep it, so that the
+        // second pass is a small elementwise kernel instead of a second sweep over the keys.  The
+        // half swap leaves the 4 key blocks of the first 32 keys in lanes 0..31, the other 4 in 32..63.
+        // Exactly one store per tile from every wavefront (the counted load waits rely on it).
+        f32x4 w;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float r0, r1;
+          if (plain) {
+            r0 = fmaxf(fmaxf(acc[0][4 * g], acc[0][4 * g + 1]), fmaxf(acc[0][4 * g + 2], acc[0][4 * g + 3])) * a.scale_log2;
+            r1 = fmaxf(fmaxf(acc[1][4 * g], acc[1][4 * g + 1]), fmaxf(acc[1][4 * g + 2], acc[1][4 * g + 3])) * a.scale_log2;
+          } else {
+            r0 = fmaxf(fmaxf(x[0][4 * g], x[0][4 * g + 1]), fmaxf(x[0][4 * g + 2], x[0][4 * g + 3]));
+            r1 = fmaxf(fmaxf(x[1][4 * g], x[1][4 * g + 1]), fmaxf(x[1][4 * g + 2], x[1][4 * g + 3]));
+          }
+          const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, r0), __builtin_bit_cast(uint32_t, r1), false, false);
+          uint32_t s0 = sw[0], s1 = sw[1];
+          asm volatile("" : "+v"(s0), "+v"(s1));
+          w[g] = fmaxf(__builtin_bit_cast(float, s0), __builtin_bit_cast(float, s1));
+        }
+        *reinterpret_cast<f32x4*>(bmax + ((int64_t)head * a.bm_rows + row) * a.bm_pitch + tile * 8 + hf * 4) = w;
+      }
     } else {
       // per lane: 8 partial results (2 halves x 4 key blocks), each over the 4 keys this lane holds.
       // The half swap pairs value g of the first half with value g of the second: afterwards lanes
@@ -539,8 +563,10 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
   // t+1 and t+2 (RI each).  (Sweep 2 writes S in batches, after a full wait, so stores never sit
   // between the loads being counted.)
   auto wait_tile = [&](int t) __attribute__((always_inline)) {
-    constexpr int G = RI;
+    constexpr int G = RI, WITH_STORES = 2 * RI + 3;    // sweep 1 keeping block maxima: one store per tile, three tiles back
     if (SWEEP == 2 && t % STAGE_TILES < 3) __builtin_amdgcn_s_waitcnt(0x0F70);   // stores of the last write-out may be in flight
+    else if (SWEEP == 1 && bmax && t >= 3 && t + 2 < nt)
+      __builtin_amdgcn_s_waitcnt((WITH_STORES & 15) | ((WITH_STORES >> 4) << 14) | 0x0F70);
     else if (t + 2 < nt) __builtin_amdgcn_s_waitcnt(((2 * G) & 15) | (((2 * G) >> 4) << 14) | 0x0F70);
     else if (t + 1 < nt) __builtin_amdgcn_s_waitcnt((G & 15) | ((G >> 4) << 14) | 0x0F70);
     else __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -566,6 +592,11 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
       if (qblk < a.nq && j < a.nk) out[(int64_t)qblk * a.nk + j] = 0.f;
     }
   }
+  if (SWEEP == 1 && bmax && nt < nt_slice) {   // key blocks of the slice that no row of this workgroup sees
+    const f32x4 ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    for (int tt = nt; tt < nt_slice; ++tt)
+      *reinterpret_cast<f32x4*>(bmax + ((int64_t)head * a.bm_rows + row) * a.bm_pitch + (t_lo + tt) * 8 + hf * 4) = ninf;
+  }
   if (SWEEP == 1) {
     float p, q;
     both_halves(l, p, q);                        // the two lane halves saw different keys
@@ -574,9 +605,36 @@ __global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __r
   }
 }
 
+// Second pass for max pooling: S[i, j] = 2^(max over the 8 rows of block i of (block maximum - lse of the row)).
+__global__ __launch_bounds__(256) void importance_finalize_kernel(const float2* __restrict__ part,
+                                                                  const float* __restrict__ bmax, float* __restrict__ S,
+                                                                  int nq, int nk, int ksplit, int bm_rows, int bm_pitch) {
+  __shared__ float lse_s[8];
+  const int tid = threadIdx.x, qi = blockIdx.x, head = blockIdx.y;
+  const int nrows = nq * 8;
+  if (tid < 8) {
+    const float2* pr = part + ((int64_t)head * nrows + qi * 8 + tid) * IMP_MAX_SPLIT;
+    float mrow = -INFINITY, lrow = 0.f;
+    for (int s2 = 0; s2 < ksplit; ++s2) mrow = fmaxf(mrow, pr[s2].x);
+    for (int s2 = 0; s2 < ksplit; ++s2) {
+      const float2 v = pr[s2];
+      if (v.x != -INFINITY) lrow += v.y * __builtin_amdgcn_exp2f(v.x - mrow);
+    }
+    lse_s[tid] = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;
+  }
+  __syncthreads();
+  const float* b0 = bmax + ((int64_t)head * bm_rows + qi * 8) * bm_pitch;
+  for (int j = tid; j < nk; j += 256) {
+    float v = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) v = fmaxf(v, b0[(int64_t)r * bm_pitch + j] - lse_s[r]);
+    S[((int64_t)head * nq + qi) * nk + j] = __builtin_amdgcn_exp2f(v);
+  }
+}
+
 template <int D>
-static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const void* Krep, float2* part, float* S,
-                                     hipStream_t s) {
+static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const void* Krep, float2* part, float* bmax,
+                                     float* S, hipStream_t s) {
   ImpTileArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.mode = pl.rep_mode; a.causal = pl.causal; a.est_pool = pl.est_pool;
@@ -604,19 +662,29 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
-  k1<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, a);
+  const bool keep_max = pl.est_pool == PSA_EST_MAX;
+  a.bm_rows = row_groups * 128;
+  a.bm_pitch = ntile_all * 8;
+  k1<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S,
+                             keep_max ? bmax : nullptr, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  k2<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, a);
+  if (keep_max) {
+    importance_finalize_kernel<<<dim3(pl.nq, pl.Hq * pl.B), 256, 0, s>>>(part, bmax, S, pl.nq, pl.nk, ksplit, a.bm_rows,
+                                                                         a.bm_pitch);
+    return hipGetLastError();
+  }
+  k2<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, nullptr, a);
   return hipGetLastError();
 }
 
 bool importance_uses_mfma(const Plan& pl) { return pl.dtype == PSA_BF16 && pl.sq == 8 && pl.sk == 8; }
 
-hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, float* S, hipStream_t s) {
+hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, void* bmax, float* S,
+                             hipStream_t s) {
   if (importance_uses_mfma(pl))
-    return pl.d == 64 ? launch_imp_tiles_t<64>(pl, Qrep, Krep, static_cast<float2*>(part), S, s)
-                      : launch_imp_tiles_t<128>(pl, Qrep, Krep, static_cast<float2*>(part), S, s);
+    return pl.d == 64 ? launch_imp_tiles_t<64>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, s)
+                      : launch_imp_tiles_t<128>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, s);
   if (pl.dtype == PSA_F32)
     return pl.d == 64 ? launch_imp_t<float, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<float, 128>(pl, Qrep, Krep, S, s);
   return pl.d == 64 ? launch_imp_t<bf16_t, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<bf16_t, 128>(pl, Qrep, Krep, S, s);

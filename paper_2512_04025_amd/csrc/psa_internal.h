@@ -21,7 +21,7 @@ struct Plan {
   bool krep_is_pyramid;         // representative keys are exactly pyramid level H
   bool use_mfma;                // bf16 tensor-core attention kernel applies
   // scratch layout (byte offsets, 256-aligned)
-  size_t off_qrep, off_krep, off_scores, off_part, off_rowcnt, off_idx, off_cnt, scratch_bytes;
+  size_t off_qrep, off_krep, off_scores, off_part, off_bmax, off_rowcnt, off_idx, off_cnt, scratch_bytes;
 };
 
 int make_plan(const psa_params* p, Plan* out);
@@ -34,7 +34,9 @@ constexpr int CNT_STRIDE = PSA_MAX_LEVELS;
 hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s);
 hipError_t launch_representatives(const Plan& pl, const void* X, void* R, bool is_query, hipStream_t s);
 // part: per (row, key slice) partial softmax statistics of the matrix-core path (Plan::off_part)
-hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, float* S, hipStream_t s);
+// bmax: per (representative row, key block) largest logit, kept for max pooling (Plan::off_bmax)
+hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, void* bmax, float* S,
+                             hipStream_t s);
 hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, uint8_t* M, uint32_t* rowcnt,
                            hipStream_t s);
 hipError_t launch_rho(const Plan& pl, const uint32_t* rowcnt, float* rho, hipStream_t s);
