@@ -1,17 +1,17 @@
 // Multi-level mask assignment (Sec. 3.3.2, Alg. 2, Eq. 5-7; quantile rule of Sec. 4.4), the
 // compute ratio of Eq. 9, and the per-row level-sorted block lists the attention kernels walk.
 //
-// alloc_kernel: one workgroup per query block.  The row of scores is turned into 64-bit keys
+// alloc_kernel: one wavefront per query block.  The row of scores is turned into 64-bit keys
 // (descending score, then ascending block index -> a stable descending sort), sorted with a bitonic
-// network in LDS, and levels are read off the sorted order: from the fp64 inclusive cumulative
-// share (Alg. 2) or from the rank against per-level quotas.
+// network held in registers, and levels are read off the sorted order: from the fp64 inclusive
+// cumulative share (Alg. 2) or from the rank against per-level quotas.
 #include "psa_dev.h"
 #include "psa_internal.h"
 
 namespace psa {
 
 struct AllocArgs {
-  int N, Hq, Hkv, nq, nk, bq, bk, H, causal, mode, P;
+  int N, Hq, Hkv, nq, nk, bq, bk, H, causal, mode;
   float tau[PSA_MAX_LEVELS];
   double cuts[PSA_MAX_LEVELS];
 };
@@ -53,16 +53,16 @@ __device__ __forceinline__ double wave_incl_scan(double x, int lane) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void alloc_kernel(const float* __restrict__ S, const uint8_t* __restrict__ cap,
-                                                    uint8_t* __restrict__ M, uint32_t* __restrict__ rowcnt,
-                                                    AllocArgs a) {
-  extern __shared__ unsigned char smem_raw[];
-  uint64_t* keys = reinterpret_cast<uint64_t*>(smem_raw);   // [P]
-  double* share = reinterpret_cast<double*>(keys + a.P);    // [P] (threshold mode)
-  __shared__ double wsum[4];
-  __shared__ int nvis_s;
+// One wavefront per query block, the whole row in registers: lane l holds the KPL keys at sorted
+// positions l*KPL .. l*KPL+KPL-1.  Bitonic stages whose partner distance is below KPL exchange
+// registers of one lane (register numbers are compile-time); longer distances exchange the same
+// register between lanes l and l ^ m.  No LDS traffic and no barrier in the sort.
+template <int KPL>
+__global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, const uint8_t* __restrict__ cap,
+                                                   uint8_t* __restrict__ M, uint32_t* __restrict__ rowcnt,
+                                                   AllocArgs a) {
   __shared__ int cnt_s[PSA_MAX_LEVELS + 1];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x;
   const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int64_t row = ((int64_t)b * a.Hq + hq) * a.nq + i;
   const float* s_row = S + row * a.nk;
@@ -70,62 +70,69 @@ __global__ __launch_bounds__(256) void alloc_kernel(const float* __restrict__ S,
   const uint8_t* cap_row = cap ? cap + ((int64_t)b * a.Hkv + hq / (a.Hq / a.Hkv)) * a.nk : nullptr;
   const bool quota = a.mode != PSA_ALLOC_THRESHOLD;
 
-  if (tid == 0) nvis_s = 0;
-  if (tid <= PSA_MAX_LEVELS) cnt_s[tid] = 0;
-  __syncthreads();
-  int my_vis = 0;
-  for (int j = tid; j < a.P; j += 256) {
-    uint64_t key = ~0ull;
+  if (lane <= PSA_MAX_LEVELS) cnt_s[lane] = 0;
+  uint64_t key[KPL];
+  int n_vis = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int j = r * 64 + lane;   // any initial placement will do; this one reads coalesced
+    uint64_t kk = ~0ull;
     if (j < a.nk) {
       const int v = block_vis(i, j, a.bq, a.bk, a.N, a.causal);
       if (v == 0) {
         m_row[j] = 0;
       } else {
         const uint32_t ord = (quota && v == 2) ? 0u : desc_bits(s_row[j]);
-        key = ((uint64_t)ord << 32) | (uint32_t)j;
-        ++my_vis;
+        kk = ((uint64_t)ord << 32) | (uint32_t)j;
+        ++n_vis;
       }
     }
-    keys[j] = key;
+    key[r] = kk;
   }
-  if (my_vis) atomicAdd(&nvis_s, my_vis);
-  __syncthreads();
-  const int n_vis = nvis_s;
+#pragma unroll
+  for (int off = 32; off; off >>= 1) n_vis += __shfl_xor(n_vis, off, 64);
 
-  // bitonic sort, ascending.  Each wavefront owns a contiguous quarter of the keys: a stage whose
-  // partner distance stays inside a quarter touches only the wavefront's own keys, and since the LDS
-  // serves one wavefront's operations in order such stages need no workgroup barrier (only a fence
-  // that keeps the compiler from moving LDS operations across).  Only the few stages with a longer
-  // distance synchronise the workgroup.
-  const int chunk = a.P >> 2;                   // keys per wavefront (P >= 256: at least 64)
-  auto exchange = [&](int t, int jj, int k) {       // jj is a power of two
-    const int lo = ((t & ~(jj - 1)) << 1) + (t & (jj - 1));
-    const int hi = lo + jj;
-    const uint64_t x = keys[lo], y = keys[hi];
-    const bool up = (lo & k) == 0;
-    if ((x > y) == up) { keys[lo] = y; keys[hi] = x; }
+  // bitonic sort, ascending over position lane*KPL + r
+  auto in_lane = [&](uint64_t& x, uint64_t& y, bool up) {
+    const bool sw = (x > y) == up;
+    const uint64_t lo = sw ? y : x;
+    y = sw ? x : y;
+    x = lo;
   };
-  bool local_before = false;
-  for (int k = 2; k <= a.P; k <<= 1) {
+#pragma unroll
+  for (int k = 2; k <= KPL; k <<= 1) {        // phases that stay inside a lane
+#pragma unroll
     for (int jj = k >> 1; jj > 0; jj >>= 1) {
-      if (a.P >= 256 && jj < chunk) {
-        for (int t = wave * (chunk >> 1) + lane; t < (wave + 1) * (chunk >> 1); t += 64) exchange(t, jj, k);
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        local_before = true;
-      } else {
-        if (local_before) __syncthreads();
-        for (int t = tid; t < (a.P >> 1); t += 256) exchange(t, jj, k);
-        __syncthreads();
-        local_before = false;
+#pragma unroll
+      for (int r = 0; r < KPL; ++r) {
+        if (r & jj) continue;
+        const bool up = k < KPL ? ((r & k) == 0) : ((lane & 1) == 0);
+        in_lane(key[r], key[r | jj], up);
       }
     }
   }
-  if (local_before) __syncthreads();
+  for (int kl = 2; kl <= 64; kl <<= 1) {      // phase k = kl * KPL
+    const bool up = (lane & kl) == 0;
+    for (int m = kl >> 1; m > 0; m >>= 1) {   // partner lane l ^ m
+      const bool keep_min = ((lane & m) == 0) == up;
+#pragma unroll
+      for (int r = 0; r < KPL; ++r) {
+        const uint64_t mine = key[r];
+        const uint64_t other = __shfl_xor((unsigned long long)mine, m, 64);
+        key[r] = ((mine < other) == keep_min) ? mine : other;
+      }
+    }
+#pragma unroll
+    for (int jj = KPL >> 1; jj > 0; jj >>= 1) {
+#pragma unroll
+      for (int r = 0; r < KPL; ++r) {
+        if (r & jj) continue;
+        in_lane(key[r], key[r | jj], up);
+      }
+    }
+  }
 
-  const int C = a.P >= 256 ? a.P / 256 : 1;   // sorted elements per thread (contiguous)
-  const int k0 = tid * C;
-
+  const int k0 = lane * KPL;
   int e_hi[PSA_MAX_LEVELS];
   double offset = 0.0, total = 1.0;
   bool uniform = false;
@@ -142,59 +149,58 @@ __global__ __launch_bounds__(256) void alloc_kernel(const float* __restrict__ S,
   } else {
     // total of the visible scores (fp64), then shares and their inclusive cumulative sum
     double part = 0.0;
-    for (int u = 0; u < C; ++u) {
-      const int k = k0 + u;
-      if (k < n_vis && k < a.P) part += (double)from_desc_bits((uint32_t)(keys[k] >> 32));
-    }
-    double red = part;
-    for (int off = 32; off; off >>= 1) red += __shfl_xor(red, off, 64);
-    if (lane == 0) wsum[wave] = red;
-    __syncthreads();
-    total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
-    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < KPL; ++r)
+      if (k0 + r < n_vis) part += (double)from_desc_bits((uint32_t)(key[r] >> 32));
+    total = part;
+#pragma unroll
+    for (int off = 32; off; off >>= 1) total += __shfl_xor(total, off, 64);
     uniform = !(total > 0.0);
     if (uniform) total = (double)n_vis;
     double local = 0.0;
-    for (int u = 0; u < C; ++u) {
-      const int k = k0 + u;
-      if (k < a.P) {
-        double sh = 0.0;
-        if (k < n_vis) sh = (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(keys[k] >> 32))) / total;
-        local += sh;
-        share[k] = local;   // inclusive within the thread's chunk
-      }
-    }
-    const double incl = wave_incl_scan(local, lane);
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    offset = incl - local;
-    for (int w = 0; w < wave; ++w) offset += wsum[w];
+#pragma unroll
+    for (int r = 0; r < KPL; ++r)
+      if (k0 + r < n_vis) local += (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(key[r] >> 32))) / total;
+    offset = wave_incl_scan(local, lane) - local;
   }
 
-  for (int u = 0; u < C; ++u) {
-    const int k = k0 + u;
-    if (k >= n_vis || k >= a.P) break;
-    const int j = (int)(uint32_t)keys[k];
-    int level = 0;
-    if (quota) {
-      for (int h = a.H - 1; h >= 0; --h)
-        if (k < e_hi[h]) level = h + 1;
-    } else {
-      const double ehat = offset + share[k];
-      for (int h = a.H - 1; h >= 0; --h)
-        if (ehat <= (double)a.tau[h]) level = h + 1;
-      if (k == 0 && level == 0) level = 1;
+  __syncthreads();   // the counters are zero
+  double run = 0.0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int k = k0 + r;
+    if (k < n_vis) {
+      const int j = (int)(uint32_t)key[r];
+      int level = 0;
+      if (quota) {
+        for (int h = a.H - 1; h >= 0; --h)
+          if (k < e_hi[h]) level = h + 1;
+      } else {
+        run += (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(key[r] >> 32))) / total;
+        const double ehat = offset + run;
+        for (int h = a.H - 1; h >= 0; --h)
+          if (ehat <= (double)a.tau[h]) level = h + 1;
+        if (k == 0 && level == 0) level = 1;
+      }
+      if (block_vis(i, j, a.bq, a.bk, a.N, a.causal) == 2) level = 1;
+      if (cap_row && level > 0) {
+        const int cj = cap_row[j];
+        level = level < cj ? level : cj;
+      }
+      m_row[j] = (uint8_t)level;
+      atomicAdd(&cnt_s[level], 1);
     }
-    if (block_vis(i, j, a.bq, a.bk, a.N, a.causal) == 2) level = 1;
-    if (cap_row && level > 0) {
-      const int cj = cap_row[j];
-      level = level < cj ? level : cj;
-    }
-    m_row[j] = (uint8_t)level;
-    atomicAdd(&cnt_s[level], 1);
   }
   __syncthreads();
-  if (tid <= a.H) rowcnt[row * ROWCNT_STRIDE + tid] = tid == 0 ? (uint32_t)n_vis : (uint32_t)cnt_s[tid];
+  if (lane <= a.H) rowcnt[row * ROWCNT_STRIDE + lane] = lane == 0 ? (uint32_t)n_vis : (uint32_t)cnt_s[lane];
+}
+
+template <int KPL>
+static hipError_t launch_alloc_t(const Plan& pl, const AllocArgs& a, const float* S, const uint8_t* cap, uint8_t* M,
+                                 uint32_t* rowcnt, hipStream_t s) {
+  dim3 grid(pl.nq, pl.Hq, pl.B);
+  alloc_kernel<KPL><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, uint8_t* M, uint32_t* rowcnt,
@@ -202,17 +208,19 @@ hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, u
   AllocArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.H = pl.H; a.causal = pl.causal; a.mode = pl.alloc_mode;
-  int P = 2;
-  while (P < pl.nk) P <<= 1;
-  a.P = P;
   for (int h = 0; h < PSA_MAX_LEVELS; ++h) { a.tau[h] = pl.tau[h]; a.cuts[h] = pl.cuts[h]; }
-  const size_t smem = (size_t)P * 16;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(alloc_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-  if (e != hipSuccess) return e;
-  dim3 grid(pl.nq, pl.Hq, pl.B);
-  alloc_kernel<<<grid, 256, smem, s>>>(S, cap, M, rowcnt, a);
-  return hipGetLastError();
+  int kpl = 1;                       // keys per lane: the row padded to a power of two >= 64
+  while (64 * kpl < pl.nk) kpl <<= 1;
+  switch (kpl) {
+    case 1:  return launch_alloc_t<1>(pl, a, S, cap, M, rowcnt, s);
+    case 2:  return launch_alloc_t<2>(pl, a, S, cap, M, rowcnt, s);
+    case 4:  return launch_alloc_t<4>(pl, a, S, cap, M, rowcnt, s);
+    case 8:  return launch_alloc_t<8>(pl, a, S, cap, M, rowcnt, s);
+    case 16: return launch_alloc_t<16>(pl, a, S, cap, M, rowcnt, s);
+    case 32: return launch_alloc_t<32>(pl, a, S, cap, M, rowcnt, s);
+    case 64: return launch_alloc_t<64>(pl, a, S, cap, M, rowcnt, s);
+    default: return hipErrorInvalidValue;   // more than PSA_MAX_NK key blocks: refused before any launch
+  }
 }
 
 // Eq. 9 per (batch, head): sum_h c_h 2^-(h-1) over the visible block pairs.
