@@ -250,9 +250,43 @@ hipError_t launch_rho(const Plan& pl, const uint32_t* rowcnt, float* rho, hipStr
 }
 
 // Per query block: the kept key blocks grouped by level (ascending block index inside a level)
-// and the number of blocks per level.  One wavefront per row.
+// and the number of blocks per level.  One wavefront per row; the row of levels is loaded once
+// into NCH registers per lane (block c*64 + lane in register c).
+template <int NCH>
 __global__ __launch_bounds__(256) void schedule_kernel(const uint8_t* __restrict__ M, uint16_t* __restrict__ idx,
                                                        int32_t* __restrict__ cnt, int64_t rows, int nk, int H) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const uint8_t* m = M + row * nk;
+  uint16_t* out = idx + row * nk;
+  int lv[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int j = c * 64 + lane;
+    lv[c] = j < nk ? (int)m[j] : 0;
+  }
+  const uint64_t below = (1ull << lane) - 1ull;
+  int pos = 0;
+  for (int h = 1; h <= PSA_MAX_LEVELS; ++h) {
+    int n = 0;
+    if (h <= H) {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const bool hit = lv[c] == h;
+        const uint64_t mask = __ballot(hit);
+        if (hit) out[pos + n + __popcll(mask & below)] = (uint16_t)(c * 64 + lane);
+        n += __popcll(mask);
+      }
+    }
+    if (lane == 0) cnt[row * CNT_STRIDE + (h - 1)] = n;
+    pos += n;
+  }
+}
+
+// The same for rows of more than 4096 blocks: the row is re-read from memory for every level.
+__global__ __launch_bounds__(256) void schedule_sweep_kernel(const uint8_t* __restrict__ M, uint16_t* __restrict__ idx,
+                                                             int32_t* __restrict__ cnt, int64_t rows, int nk, int H) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -275,9 +309,29 @@ __global__ __launch_bounds__(256) void schedule_kernel(const uint8_t* __restrict
   }
 }
 
+template <int NCH>
+static hipError_t launch_schedule_t(const uint8_t* M, uint16_t* idx, int32_t* cnt, int64_t rows, int nk, int H,
+                                    hipStream_t s) {
+  schedule_kernel<NCH><<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(M, idx, cnt, rows, nk, H);
+  return hipGetLastError();
+}
+
 hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int32_t* cnt, hipStream_t s) {
   const int64_t rows = (int64_t)pl.B * pl.Hq * pl.nq;
-  schedule_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(M, idx, cnt, rows, pl.nk, pl.H);
+  int nch = 1;
+  while (64 * nch < pl.nk) nch <<= 1;
+  switch (nch) {
+    case 1:  return launch_schedule_t<1>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 2:  return launch_schedule_t<2>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 4:  return launch_schedule_t<4>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 8:  return launch_schedule_t<8>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 16: return launch_schedule_t<16>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 32: return launch_schedule_t<32>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    case 64: return launch_schedule_t<64>(M, idx, cnt, rows, pl.nk, pl.H, s);
+    default: break;
+  }
+  // longer rows do not fit the registers of one wavefront: sweep the row once per level instead
+  schedule_sweep_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(M, idx, cnt, rows, pl.nk, pl.H);
   return hipGetLastError();
 }
 

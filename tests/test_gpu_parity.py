@@ -48,6 +48,8 @@ def _case(name):
             "edge_bq96": base.with_(N=700, grid=(1, 20, 35), bq=96, bk=64, levels=3),     # rows kernel fallback
             "edge_eight_levels": base.with_(N=2048, grid=(2, 32, 32), bq=128, bk=128, levels=8),
         }[name], {}
+    if name == "long_rows":       # more than 4096 key blocks per row (sparse masks only: the allocation entry point refuses it)
+        return si.small_variant(C["dit1p3b"], 32 * 4200 - 5, Hq=1, Hkv=1).with_(bq=32, bk=32, levels=3), {}
     if name == "f32_d128":
         return si.small_variant(C["dit1p3b"], 520, Hq=2, Hkv=1).with_(dtype="f32"), {}
     raise KeyError(name)
@@ -284,6 +286,23 @@ def test_attention_random_masks(name):
     M = np.where(vis[None, None] == 0, 0, M)
     M = np.where(vis[None, None] == 2, 1, M).astype(np.uint8)
     _attention_case(name, {}, mask=M)
+
+
+def test_attention_rows_longer_than_the_allocation_limit():
+    """A caller-made mask over 4200 key blocks per row: the block lists are built by the sweep that
+    re-reads the row per level."""
+    w, _ = _case("long_rows")
+    op = oracle_params(w)
+    assert op.nk > 4096
+    rng = np.random.default_rng(5)
+    M = np.zeros((op.B, op.Hq, op.nq, op.nk), dtype=np.uint8)
+    for i in range(op.nq):
+        cols = rng.choice(op.nk, size=6, replace=False)
+        M[0, 0, i, cols] = rng.integers(1, op.levels + 1, size=6)
+    M[..., 0] = 1
+    M[0, 0, 7] = 0
+    M[0, 0, 7, op.nk - 1] = 3                                        # only the last, partial block, coarsest level
+    _attention_case("long_rows", {}, mask=M)
 
 
 def test_all_level1_mask_equals_dense_ref():
