@@ -456,7 +456,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const int e = 2 * q, mb = e >> 4, v = e & 15;
     const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v], a.scale_log2, shift));
     const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[mb][v + 1], a.scale_log2, shift));
-    l_run += p0 + p1;
+    l_run += p0;   // two dependent adds, not p0 + p1 first: the first use of a transcendental result must not directly follow it
+    l_run += p1;
     bf16x2 pk;
     pk[0] = (__bf16)p0;
     pk[1] = (__bf16)p1;
@@ -548,7 +549,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
           const int e = (j * MPC + u) * 2, mb = e >> 4, v = e & 15;
           rawmax = fmaxf(rawmax, fmaxf(sn[mb][v], sn[mb][v + 1]));
         }
-        asm volatile("" : "+v"(rawmax));
+        asm volatile("" :: "v"(rawmax));   // computed here; input only: a register an assembly statement names as output may not be read by the next vector instruction without a padding s_nop
       }
       __builtin_amdgcn_sched_barrier(0);
     }
