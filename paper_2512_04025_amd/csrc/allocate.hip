@@ -335,4 +335,71 @@ hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int3
   return hipGetLastError();
 }
 
+// Tile descriptors for the matrix-core attention kernel.  The kept blocks of a level, in list order,
+// form one stream of pooled tokens that is cut into tiles of 64; tile row r of a tile comes from
+// pooled row (block id << lg_th) | (stream position & (th - 1)) of the level's array.  A tile is
+// irregular when some row lies past the level's kept blocks, covers tokens past N, or (causal) is not
+// visible to every query row of the block.  One word per load instruction of the kernel (rpi tile
+// rows each), stored per wavefront, [row][wavefront][tile][ri]: word k of wavefront w belongs to load
+// instruction k*nw + w, and a wavefront's descriptors of consecutive tiles are adjacent in memory.  Byte offset of the instruction's first source row; the first word of
+// each wavefront also carries level - 1 in bits 0..3 and the irregular flag in bit 4 (row offsets are
+// multiples of 128 bytes).  Four null tiles (level field 15) follow the last one: the kernel
+// requests tiles ahead of the one it computes (and touches one cache line further: the pitch leaves room).
+struct TileArgs {
+  int N, nq, nk, bq, lg_bk, H, causal, rowb, rpi, nw, ri, words, pitch;
+};
+
+__global__ __launch_bounds__(256) void tiles_kernel(const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                    uint32_t* __restrict__ desc, int64_t rows, TileArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const uint16_t* lst = idx + row * a.nk;
+  const int32_t* c = cnt + row * CNT_STRIDE;
+  uint32_t* drow = desc + row * (int64_t)a.pitch * a.words;
+  const int i = (int)(row % a.nq);
+  const int q = lane / a.rpi, w = q % a.nw, k = q / a.nw;
+  const bool writer = lane % a.rpi == 0;
+  int tt = 0, start = 0;
+  for (int h = 1; h <= a.H; ++h) {
+    const int nb = c[h - 1];
+    if (nb == 0) continue;
+    const int lg_th = a.lg_bk - (h - 1);
+    const int ntl = ((nb << lg_th) + 63) >> 6;
+    int lim = a.N >> (h - 1);                       // rows below cover 2^(h-1) valid tokens
+    if (a.causal) {
+      const int vis = (i * a.bq + 1) >> (h - 1);    // rows below end at or before the block's first query row
+      lim = vis < lim ? vis : lim;
+    }
+    for (int tl = 0; tl < ntl; ++tl, ++tt) {
+      const int g = (tl << 6) + lane, e = g >> lg_th;
+      const int jl = (int)lst[start + (e < nb ? e : nb - 1)];
+      const int prow = (jl << lg_th) | (g & ((1 << lg_th) - 1));
+      const bool irregular = __ballot((e >= nb) | (prow >= lim)) != 0ull;
+      if (writer)
+        drow[((int64_t)w * a.pitch + tt) * a.ri + k] =
+            (uint32_t)prow * (uint32_t)a.rowb | (k == 0 ? (uint32_t)(h - 1) | (irregular ? 16u : 0u) : 0u);
+    }
+    start += nb;
+  }
+  for (int x = 0; x < 4; ++x)
+    if (lane < a.words) drow[((int64_t)(lane / a.ri) * a.pitch + tt + x) * a.ri + lane % a.ri] = lane % a.ri == 0 ? 15u : 0u;
+}
+
+hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt, uint32_t* desc, hipStream_t s) {
+  TileArgs a;
+  a.N = pl.N; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.H = pl.H; a.causal = pl.causal;
+  a.lg_bk = 0;
+  while ((1 << a.lg_bk) < pl.bk) ++a.lg_bk;
+  a.rowb = pl.d * 2;
+  a.words = pl.desc_words;
+  a.rpi = 64 / a.words;
+  a.nw = 4;
+  a.ri = a.words / a.nw;
+  a.pitch = pl.desc_pitch;
+  const int64_t rows = (int64_t)pl.B * pl.Hq * pl.nq;
+  tiles_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(idx, cnt, desc, rows, a);
+  return hipGetLastError();
+}
+
 }  // namespace psa

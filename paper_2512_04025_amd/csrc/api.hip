@@ -70,6 +70,13 @@ int make_plan(const psa_params* p, Plan* o) {
   o->off_rowcnt = s; s += align256(rows_q * ROWCNT_STRIDE * sizeof(uint32_t));
   o->off_idx = s;    s += align256(rows_q * o->nk * sizeof(uint16_t));
   o->off_cnt = s;    s += align256(rows_q * CNT_STRIDE * sizeof(int32_t));
+  {  // tile descriptors: full 128-row workgroups whose load instructions (64 lanes x 16 B) never straddle a pooled block
+    const int rows_per_load = 64 / (o->d / 8);
+    const bool used = o->use_mfma && o->bq % 128 == 0 && (o->bk >> (o->H - 1)) >= rows_per_load;
+    o->desc_words = o->d / 8;
+    o->desc_pitch = used ? (int)(((int64_t)o->nk * o->bk + 63) >> 6) + o->H + 4 + 16 : 0;   // + null tiles + room for the look-ahead touch
+    o->off_desc = s;   s += align256(rows_q * (size_t)o->desc_pitch * o->desc_words * sizeof(uint32_t));
+  }
   o->scratch_bytes = s;
   return PSA_OK;
 }
@@ -191,7 +198,9 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
   uint16_t* idx = reinterpret_cast<uint16_t*>(at(scratch, pl.off_idx));
   int32_t* cnt = reinterpret_cast<int32_t*>(at(scratch, pl.off_cnt));
   if (launch_schedule(pl, M, idx, cnt, s) != hipSuccess) return PSA_ELAUNCH;
-  const hipError_t e = pl.use_mfma ? launch_attn_mfma(pl, Q, K, V, Kpyr, Vpyr, idx, cnt, O, lse, s)
+  uint32_t* desc = reinterpret_cast<uint32_t*>(at(scratch, pl.off_desc));
+  if (pl.desc_pitch > 0 && launch_tiles(pl, idx, cnt, desc, s) != hipSuccess) return PSA_ELAUNCH;
+  const hipError_t e = pl.use_mfma ? launch_attn_mfma(pl, Q, K, V, Kpyr, Vpyr, idx, cnt, desc, O, lse, s)
                                    : launch_attn_rows(pl, Q, K, V, Kpyr, Vpyr, idx, cnt, O, lse, s);
   return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }

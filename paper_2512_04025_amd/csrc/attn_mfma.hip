@@ -41,6 +41,7 @@ struct MfmaArgs {
   int lg_bk;
   int slices;              // workgroup slices per query block
   int items;               // B * Hq * nq * slices
+  int desc_pitch;          // tile descriptors per row (0: the kernel plans its loads itself)
   float scale_log2;        // scale * log2(e)
   int64_t lvl_off[PSA_MAX_LEVELS + 2];
 };
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(BN == 3
 void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                       const bf16_t* __restrict__ Kp, const bf16_t* __restrict__ Vp,
                       const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
-                      bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
+                      const uint32_t* __restrict__ desc, bf16_t* __restrict__ O, float* __restrict__ lse, MfmaArgs a) {
   constexpr int NT = NW * 64;
   constexpr int ROWS = NW * 32;              // query rows per workgroup
   constexpr int CPR = D / 8;                 // 16-byte chunks per row
@@ -95,6 +96,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   constexpr int NA = HALVES * (D / 16);      // MFMAs of S^T = K Q^T per tile
   constexpr int NB = (BN / 16) * (D / 32);   // MFMAs of O^T += V^T P^T per tile
   constexpr int MPC = NPAIR / NB;            // 3-input maxima handled next to one MFMA of the second product
+  // Full-size workgroups on shapes whose load instructions never straddle a pooled block read their
+  // load plan from per-tile descriptors made by tiles_kernel instead of deriving it per tile.
+  constexpr bool DESC = SC && BN == 64 && NW == 4;
   static_assert(BN == 64 || BN == 32, "tile width");
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
   static_assert(MPC * NB == NPAIR, "chunking of the softmax work");
@@ -291,6 +295,59 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
+  // ---- tile descriptors (DESC).  tiles_kernel has worked out, per tile and load instruction, what the
+  // planner above derives: RI consecutive words per wavefront and tile, each the byte offset of the
+  // source row of one of this wavefront's loads; the low bits of the first word carry the tile's
+  // level - 1 (15: a null tile past the end of the row) and, in bit 4, whether the tile is irregular.
+  // They arrive through scalar loads issued half a step before they are used, so the per-tile
+  // bookkeeping is a handful of scalar instructions and nothing rotates through registers.
+  static_assert(!DESC || RI == 4 || RI == 2, "descriptor words per wavefront");
+  typedef uint32_t descv __attribute__((ext_vector_type(RI == 4 ? 4 : 2)));
+  const uint32_t* dbase = DESC ? desc + ((srow * NW + wave) * (int64_t)a.desc_pitch) * RI : nullptr;   // [row][wavefront][tile][RI]
+  auto desc_load = [&](descv& d, int t) __attribute__((always_inline)) {
+    const uint32_t off = (uint32_t)t * (uint32_t)(RI * 4);
+    if constexpr (RI == 4) asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(d) : "s"(dbase), "s"(off));
+    else asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(d) : "s"(dbase), "s"(off));
+  };
+  // Scalar loads share the LDS counter.  One in flight only makes the counted fragment waits stricter
+  // (a wait for "at most n outstanding" is reached after at least as many LDS completions as without it).
+  // One wavefront's descriptors are consecutive, a 64-byte line holds those of 64 / (4 RI) tiles; the
+  // line after the one being read is touched ahead of time (the word itself is not used, but its
+  // register stays reserved until the next wait: the load may still be in flight).
+  uint32_t dtouch = 0u;
+  auto desc_touch = [&](int t) __attribute__((always_inline)) {
+    const uint32_t off = (uint32_t)t * (uint32_t)(RI * 4) + 64u;
+    asm volatile("s_load_dword %0, %1, %2" : "=s"(dtouch) : "s"(dbase), "s"(off));
+  };
+  auto desc_wait = [&](descv& d) __attribute__((always_inline)) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d), "+s"(dtouch)); };
+  struct Stream {            // the level the K (or V) loads are currently reading from
+    int lvl;                 // level - 1; 15 = null tiles; -1 = none yet
+    const char* base;
+    uint32_t nrec;
+  };
+  Stream kst{-1, reinterpret_cast<const char*>(K), 0u}, vst{-1, reinterpret_cast<const char*>(V), 0u};
+  auto set_level = [&](Stream& st, int m, bool is_k) __attribute__((always_inline)) {   // once per level change
+    st.lvl = m;
+    if (m == 15) { st.nrec = 0u; return; }
+    const int64_t rows_h = (int64_t)a.nk << (a.lg_bk - m);
+    st.nrec = (uint32_t)(m == 0 ? (int64_t)a.N : rows_h) * (uint32_t)(D * 2);
+    if (m == 0) st.base = reinterpret_cast<const char*>((is_k ? K : V) + khead * (int64_t)a.N * D);
+    else st.base = reinterpret_cast<const char*>((is_k ? Kp : Vp) + a.lvl_off[m + 1] + khead * rows_h * D);
+  };
+  auto fire_desc = [&](const descv& d, Stream& st, bool is_k, int t) __attribute__((always_inline)) {
+    const int m = (int)(d[0] & 15u);
+    if (m != st.lvl) set_level(st, m, is_k);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)st.base, 0, (int)st.nrec, RSRC_FLAGS);
+#pragma unroll
+    for (int k = 0; k < RI; ++k) {
+      const uint32_t off = k == 0 ? (d[0] & ~127u) : d[k % (RI == 4 ? 4 : 2)];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + (is_k ? OFF_K : OFF_V) + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
+                                               16, (int)(off + (is_k ? klane[k % KP] : vlane[k % KP])), 0, 0, 0);
+    }
+  };
+  descv dK, dV;              // descriptors of the tile whose K rows / V rows go out next
+  uint32_t meta_next = 0u;   // low bits of the descriptor of the tile whose scores are being made
+
   // ---- query fragments (B operand of S^T = K Q^T): lane holds one row, 8 channels per k-step
   bf16x8 qf[D / 16];
   {
@@ -429,8 +486,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // Running maximum after seeing tile t whose raw-score maximum (per lane) is `rawmax`; returns the
   // constant of the exponent, p = 2^(scale*s + shift).  The maximum only advances when it grows by
   // more than LAZY_RESCALE, so the accumulator rescale is off the common path.
-  auto advance_max = [&](float rawmax, int t) __attribute__((always_inline)) -> float {
-    const float tbias = (float)((lvl_ring >> (4 * (t & 7))) & 15u);
+  auto advance_max = [&](float rawmax, float tbias) __attribute__((always_inline)) -> float {
     float tmax = rawmax * a.scale_log2 + tbias;
     {
       float p, q;
@@ -497,7 +553,15 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const bool has_next = t + 1 < total_tiles;
     wait_loads(true);                         // K(t+1): only V(t) and K(t+2) were requested after it
     wg_barrier();                             // ... everyone's part of it; the buffer of V(t-1) is free
-    fire_v(t + 1);
+    if constexpr (DESC) {
+      desc_wait(dV);
+      meta_next = dV[0] & 31u;
+      fire_desc(dV, vst, false, t + 1);
+      desc_load(dK, t + 3);
+      desc_touch(t + 3);
+    } else {
+      fire_v(t + 1);
+    }
     constexpr uint32_t flip_n = PAR ? 0u : (uint32_t)TILEB;
     constexpr uint32_t flip_c = PAR ? (uint32_t)TILEB : 0u;
     bf16x8 pf[BN / 16];
@@ -516,17 +580,24 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
         take_k(fr[j & 3], (j + PF < NA ? j + PF : NA - 1) - j);
         sn[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[j & 3], qf[ks], ks == 0 ? zero16 : sn[mb], 0, 0, 0);
       }
-      if (j == NA / 2 && k4) plan_read();
+      if (!DESC && j == NA / 2 && k4) plan_read();
 #pragma unroll
       for (int q = (j * NPA) / NA; q < ((j + 1) * NPA) / NA; ++q) exp_pair(sc, pf, shift_cur, q);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (k4) plan_resolve();
+    if (!DESC && k4) plan_resolve();
     wait_loads(true);                         // V(t): only K(t+2) and V(t+1) were requested after it
     wg_barrier();                             // ... everyone's part of it; the buffer of K(t+1) is free
-    if (k3) fire_k(t + 3);
-    rotate_plans();
-    if (has_next && ((spec_ring >> ((t + 1) & 7)) & 1u)) fixup_special(sn, t + 1);
+    if constexpr (DESC) {
+      desc_wait(dK);
+      fire_desc(dK, kst, true, t + 3);
+      desc_load(dV, t + 2);
+      if (has_next && (meta_next & 16u)) fixup_special(sn, t + 1);
+    } else {
+      if (k3) fire_k(t + 3);
+      rotate_plans();
+      if (has_next && ((spec_ring >> ((t + 1) & 7)) & 1u)) fixup_special(sn, t + 1);
+    }
     __builtin_amdgcn_sched_barrier(0);
     s16x4 vlo[4], vhi[4];
 #pragma unroll
@@ -539,7 +610,7 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       const bf16x8 vfrag = take_vt(vlo[j & 3], vhi[j & 3], 2 * ((j + PF < NB ? j + PF : NB - 1) - j));
       oacc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag, pf[ks], oacc[md], 0, 0, 0);
       if (j % BSTRIDE == 0 && NPA + j / BSTRIDE < NPAIR) exp_pair(sc, pf, shift_cur, NPA + j / BSTRIDE);
-      if (k4) {
+      if (!DESC && k4) {
 #pragma unroll
         for (int k = j; k < RI; k += NB) plan_part(k);
       }
@@ -553,8 +624,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (k4) plan_end(t + 4);
-    if (has_next) shift_cur = advance_max(rawmax, t + 1);
+    if (!DESC && k4) plan_end(t + 4);
+    if (has_next) shift_cur = advance_max(rawmax, DESC ? (float)(meta_next & 15u) : (float)((lvl_ring >> (4 * ((t + 1) & 7))) & 15u));
   };
 
   f32x16 sA[HALVES], sB[HALVES];
@@ -572,22 +643,36 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       for (int k = 0; k < RI; ++k) plan_part(k);
       plan_end(tp);
     };
-    plan_whole(0);
-    fire_k(0);
-    rotate_plans();                          // V2 = plan 0
-    rotate_plans();                          // V1 = plan 0
-    fire_v(0);
-    plan_whole(1);
-    fire_k(1);
+    descv d2;
+    if constexpr (DESC) {
+      descv d0, d1;
+      desc_load(d0, 0);
+      desc_load(d1, 1);
+      desc_load(d2, 2);
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d0), "+s"(d1), "+s"(d2));
+      fire_desc(d0, kst, true, 0);
+      fire_desc(d0, vst, false, 0);
+      fire_desc(d1, kst, true, 1);
+      meta_next = d0[0] & 31u;
+      dV = d1;                               // step 0 sends the V rows of tile 1
+    } else {
+      plan_whole(0);
+      fire_k(0);
+      rotate_plans();                          // V2 = plan 0
+      rotate_plans();                          // V1 = plan 0
+      fire_v(0);
+      plan_whole(1);
+      fire_k(1);
 #pragma unroll
-    for (int k = 0; k < RI; ++k) planV1[k] = planK[k];     // V1 = plan 1
-    planV1_vbase = planK_vbase;
-    planV1_nrec = planK_nrec;
-    plan_whole(2);                           // K(2) goes out once the scores of tile 0 are done
+      for (int k = 0; k < RI; ++k) planV1[k] = planK[k];     // V1 = plan 1
+      planV1_vbase = planK_vbase;
+      planV1_nrec = planK_nrec;
+      plan_whole(2);                           // K(2) goes out once the scores of tile 0 are done
 #pragma unroll
-    for (int k = 0; k < RI; ++k) planV2[k] = planK[k];     // V2 = plan 2
-    planV2_vbase = planK_vbase;
-    planV2_nrec = planK_nrec;
+      for (int k = 0; k < RI; ++k) planV2[k] = planK[k];     // V2 = plan 2
+      planV2_vbase = planK_vbase;
+      planV2_nrec = planK_nrec;
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     wg_barrier();
 #pragma unroll
@@ -595,17 +680,21 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
       const int mb = j % HALVES, ks = j / HALVES;
       sA[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k(j, 0u), qf[ks], ks == 0 ? zero16 : sA[mb], 0, 0, 0);
     }
-    if (spec_ring & 1u) fixup_special(sA, 0);
+    if (DESC ? (meta_next & 16u) != 0u : (spec_ring & 1u) != 0u) fixup_special(sA, 0);
     float rawmax = -INFINITY;
 #pragma unroll
     for (int mb = 0; mb < HALVES; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) rawmax = fmaxf(rawmax, sA[mb][v]);
-    shift_cur = advance_max(rawmax, 0);
+    shift_cur = advance_max(rawmax, DESC ? (float)(meta_next & 15u) : (float)(lvl_ring & 15u));
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     wg_barrier();                            // every wavefront has read K(0): its buffer takes K(2)
-    fire_k(2);
-    plan_whole(3);
+    if constexpr (DESC) {
+      fire_desc(d2, kst, true, 2);
+    } else {
+      fire_k(2);
+      plan_whole(3);
+    }
   }
   {
     const std::integral_constant<int, 0> even;
@@ -617,6 +706,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     }
     if (t < total_tiles) step(even, sA, sB, t);
     __builtin_amdgcn_s_waitcnt(0x0F70);      // the null tiles still in flight write LDS: drain before the workgroup ends
+    if constexpr (DESC) {                   // ... and the last descriptor loads still name registers
+      if (total_tiles > 0) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(dK), "+s"(dV), "+s"(dtouch));
+    }
   }
 
   // ---- epilogue: O = o / l ; lane (row, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
@@ -647,8 +739,8 @@ size_t attn_mfma_smem_bytes(int d, int nk, int bn) {
 
 template <int D, int NW, bool SC, int BN>
 static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
-                                const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
-                                hipStream_t s) {
+                                const void* Vp, const uint16_t* idx, const int32_t* cnt, const uint32_t* desc, void* O,
+                                float* lse, hipStream_t s) {
   MfmaArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.H = pl.H; a.causal = pl.causal;
@@ -658,6 +750,7 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   a.slices = (pl.bq + ROWS - 1) / ROWS;
   a.items = pl.B * pl.Hq * pl.nq * a.slices;
   a.scale_log2 = pl.scale * 1.44269504088896340736f;
+  a.desc_pitch = pl.desc_pitch;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
   const size_t smem = attn_mfma_smem_bytes(D, pl.nk, BN);
   auto kern = attn_mfma_kernel<D, NW, SC, BN>;
@@ -666,36 +759,37 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   if (e != hipSuccess) return e;
   kern<<<((a.items + 7) / 8) * 8, NW * 64, smem, s>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
-      static_cast<const bf16_t*>(Kp), static_cast<const bf16_t*>(Vp), idx, cnt, static_cast<bf16_t*>(O), lse, a);
+      static_cast<const bf16_t*>(Kp), static_cast<const bf16_t*>(Vp), idx, cnt, desc, static_cast<bf16_t*>(O), lse, a);
   return hipGetLastError();
 }
 
 template <int D, int NW>
 static hipError_t launch_mfma_d(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
-                                const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
-                                hipStream_t s) {
+                                const void* Vp, const uint16_t* idx, const int32_t* cnt, const uint32_t* desc, void* O,
+                                float* lse, hipStream_t s) {
   constexpr int RPI = 64 / (D / 8);           // tile rows per wave-wide 16 B/lane load
-  const bool blocks_cover_a_load = (pl.bk >> (pl.H - 1)) >= RPI;
+  // (the scalar-plan variant of full workgroups reads tile descriptors; without them take the general one)
+  const bool blocks_cover_a_load = (pl.bk >> (pl.H - 1)) >= RPI && (NW != 4 || pl.desc_pitch > 0);
   constexpr int BN = PSA_ATTN_TILE;
-  return blocks_cover_a_load ? launch_mfma_t<D, NW, true, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s)
-                             : launch_mfma_t<D, NW, false, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+  return blocks_cover_a_load ? launch_mfma_t<D, NW, true, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s)
+                             : launch_mfma_t<D, NW, false, BN>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
 }
 
 hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
-                            const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
-                            hipStream_t s) {
+                            const void* Vp, const uint16_t* idx, const int32_t* cnt, const uint32_t* desc, void* O,
+                            float* lse, hipStream_t s) {
   const int rows = pl.bq < 128 ? pl.bq : 128;   // rows per workgroup
   if (pl.d == 128) {
     switch (rows) {
-      case 32: return launch_mfma_d<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_d<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_d<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_d<128, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
+      case 64: return launch_mfma_d<128, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
+      case 128: return launch_mfma_d<128, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
     }
   } else if (pl.d == 64) {
     switch (rows) {
-      case 32: return launch_mfma_d<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 64: return launch_mfma_d<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
-      case 128: return launch_mfma_d<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, O, lse, s);
+      case 32: return launch_mfma_d<64, 1>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
+      case 64: return launch_mfma_d<64, 2>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
+      case 128: return launch_mfma_d<64, 4>(pl, Q, K, V, Kp, Vp, idx, cnt, desc, O, lse, s);
     }
   }
   return hipErrorInvalidValue;

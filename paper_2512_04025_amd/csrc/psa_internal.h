@@ -20,8 +20,10 @@ struct Plan {
   double cuts[PSA_MAX_LEVELS];  // cumulative block quotas (QUANTILE / BUDGET)
   bool krep_is_pyramid;         // representative keys are exactly pyramid level H
   bool use_mfma;                // bf16 tensor-core attention kernel applies
+  int desc_pitch;               // tile descriptors per query block for the attention kernel (0: not used)
+  int desc_words;               // 32-bit words per tile descriptor: one per load instruction of a 64-row tile
   // scratch layout (byte offsets, 256-aligned)
-  size_t off_qrep, off_krep, off_scores, off_part, off_bmax, off_rowcnt, off_idx, off_cnt, scratch_bytes;
+  size_t off_qrep, off_krep, off_scores, off_part, off_bmax, off_rowcnt, off_idx, off_cnt, off_desc, scratch_bytes;
 };
 
 int make_plan(const psa_params* p, Plan* out);
@@ -41,12 +43,15 @@ hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, u
                            hipStream_t s);
 hipError_t launch_rho(const Plan& pl, const uint32_t* rowcnt, float* rho, hipStream_t s);
 hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int32_t* cnt, hipStream_t s);
+// Per query block and 64-column tile of its level-sorted block list: source-row offsets of the tile's
+// load instructions, level and irregularity (Plan::off_desc; only when Plan::desc_pitch > 0)
+hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt, uint32_t* desc, hipStream_t s);
 // idx == nullptr selects dense attention (every key block at level 1)
 hipError_t launch_attn_rows(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
                             const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
                             hipStream_t s);
 hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
-                            const void* Vp, const uint16_t* idx, const int32_t* cnt, void* O, float* lse,
-                            hipStream_t s);
+                            const void* Vp, const uint16_t* idx, const int32_t* cnt, const uint32_t* desc, void* O,
+                            float* lse, hipStream_t s);
 
 }  // namespace psa
