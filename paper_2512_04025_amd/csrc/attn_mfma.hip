@@ -300,7 +300,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   // source row of one of this wavefront's loads; the low bits of the first word carry the tile's
   // level - 1 (15: a null tile past the end of the row) and, in bit 4, whether the tile is irregular.
   // They arrive through scalar loads issued half a step before they are used, so the per-tile
-  // bookkeeping is a handful of scalar instructions and nothing rotates through registers.
+  // bookkeeping is a handful of scalar instructions and nothing rotates through registers.  Scalar
+  // loads return out of order, so a wait for one drains all: there is one drain per step, and the
+  // only load that can miss the scalar cache (the look-ahead touch) is issued right after it.
   static_assert(!DESC || RI == 4 || RI == 2, "descriptor words per wavefront");
   typedef uint32_t descv __attribute__((ext_vector_type(RI == 4 ? 4 : 2)));
   const uint32_t* dbase = DESC ? desc + ((srow * NW + wave) * (int64_t)a.desc_pitch) * RI : nullptr;   // [row][wavefront][tile][RI]
@@ -319,7 +321,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const uint32_t off = (uint32_t)t * (uint32_t)(RI * 4) + 64u;
     asm volatile("s_load_dword %0, %1, %2" : "=s"(dtouch) : "s"(dbase), "s"(off));
   };
-  auto desc_wait = [&](descv& d) __attribute__((always_inline)) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d), "+s"(dtouch)); };
+  auto desc_wait = [&](descv& d, descv& e) __attribute__((always_inline)) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d), "+s"(e), "+s"(dtouch));
+  };
   struct Stream {            // the level the K (or V) loads are currently reading from
     int lvl;                 // level - 1; 15 = null tiles; -1 = none yet
     const char* base;
@@ -553,12 +557,11 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     const bool has_next = t + 1 < total_tiles;
     wait_loads(true);                         // K(t+1): only V(t) and K(t+2) were requested after it
     wg_barrier();                             // ... everyone's part of it; the buffer of V(t-1) is free
-    if constexpr (DESC) {
-      desc_wait(dV);
+    if constexpr (DESC) {                     // (both descriptors were waited for in the middle of the last step)
       meta_next = dV[0] & 31u;
       fire_desc(dV, vst, false, t + 1);
-      desc_load(dK, t + 3);
-      desc_touch(t + 3);
+      desc_load(dK, t + 3);                   // cache hits: their line was touched at least a step ago
+      desc_load(dV, t + 2);
     } else {
       fire_v(t + 1);
     }
@@ -589,9 +592,9 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     wait_loads(true);                         // V(t): only K(t+2) and V(t+1) were requested after it
     wg_barrier();                             // ... everyone's part of it; the buffer of K(t+1) is free
     if constexpr (DESC) {
-      desc_wait(dK);
+      desc_wait(dK, dV);                      // the only drain of scalar loads in a step
       fire_desc(dK, kst, true, t + 3);
-      desc_load(dV, t + 2);
+      desc_touch(t + 3);                      // has a whole step to arrive before the next drain
       if (has_next && (meta_next & 16u)) fixup_special(sn, t + 1);
     } else {
       if (k3) fire_k(t + 3);
