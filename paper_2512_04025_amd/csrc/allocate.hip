@@ -346,44 +346,59 @@ hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int3
 // multiples of 128 bytes).  Four null tiles (level field 15) follow the last one: the kernel
 // requests tiles ahead of the one it computes (and touches one cache line further: the pitch leaves room).
 struct TileArgs {
-  int N, nq, nk, bq, lg_bk, H, causal, rowb, rpi, nw, ri, words, pitch;
+  int N, nq, nk, bq, lg_bk, H, causal, rowb, rpi, nw, ri, words, pitch, lg_nw, lg_words;
 };
 
 __global__ __launch_bounds__(256) void tiles_kernel(const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
-                                                    uint32_t* __restrict__ desc, int64_t rows, TileArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
-  const uint16_t* lst = idx + row * a.nk;
+                                                    uint32_t* __restrict__ desc, TileArgs a) {
+  // one workgroup per query block; per level (wave-uniform constants), one thread per (tile, load
+  // instruction): every word is independent.  Pooled blocks hold at least rpi rows here, so the rpi
+  // rows of an instruction share their block.
+  extern __shared__ uint16_t lst[];                   // the row's block list: the gathers below hit LDS, not memory
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int64_t row = blockIdx.x;
   const int32_t* c = cnt + row * CNT_STRIDE;
   uint32_t* drow = desc + row * (int64_t)a.pitch * a.words;
   const int i = (int)(row % a.nq);
-  const int q = lane / a.rpi, w = q % a.nw, k = q / a.nw;
-  const bool writer = lane % a.rpi == 0;
-  int tt = 0, start = 0;
-  for (int h = 1; h <= a.H; ++h) {
-    const int nb = c[h - 1];
+  {  // the whole list row (entries past the kept blocks are never used): no dependence on the counts
+    const uint16_t* src = idx + row * a.nk;
+    for (int x = tid; x < a.nk; x += 256) lst[x] = src[x];
+  }
+  __syncthreads();
+  const int q = tid & (a.words - 1), w = q & (a.nw - 1), k = q >> a.lg_nw;     // words, nw: powers of two
+  const int sub = tid >> a.lg_words, per_pass = 256 >> a.lg_words;               // tiles per pass of the workgroup
+  const uint64_t group_mask = ((1ull << a.words) - 1ull) << ((lane >> a.lg_words) << a.lg_words);
+  uint32_t* dmine = drow + (int64_t)w * a.pitch * a.ri + k;
+  int nb_h[PSA_MAX_LEVELS];                            // all counts first: one round trip to memory
+#pragma unroll
+  for (int h = 0; h < PSA_MAX_LEVELS; ++h) nb_h[h] = h < a.H ? c[h] : 0;
+  int first = 0, start = 0;
+#pragma unroll
+  for (int h = 0; h < PSA_MAX_LEVELS; ++h) {           // h = level - 1
+    const int nb = nb_h[h];
     if (nb == 0) continue;
-    const int lg_th = a.lg_bk - (h - 1);
+    const int lg_th = a.lg_bk - h;
     const int ntl = ((nb << lg_th) + 63) >> 6;
-    int lim = a.N >> (h - 1);                       // rows below cover 2^(h-1) valid tokens
+    int lim = a.N >> h;                                // rows below cover 2^h valid tokens
     if (a.causal) {
-      const int vis = (i * a.bq + 1) >> (h - 1);    // rows below end at or before the block's first query row
+      const int vis = (i * a.bq + 1) >> h;             // rows below end at or before the block's first query row
       lim = vis < lim ? vis : lim;
     }
-    for (int tl = 0; tl < ntl; ++tl, ++tt) {
-      const int g = (tl << 6) + lane, e = g >> lg_th;
+    for (int t0 = 0; t0 < ntl; t0 += per_pass) {
+      const int tl = t0 + sub;
+      const int g = (tl << 6) + q * a.rpi, e = g >> lg_th;
       const int jl = (int)lst[start + (e < nb ? e : nb - 1)];
       const int prow = (jl << lg_th) | (g & ((1 << lg_th) - 1));
-      const bool irregular = __ballot((e >= nb) | (prow >= lim)) != 0ull;
-      if (writer)
-        drow[((int64_t)w * a.pitch + tt) * a.ri + k] =
-            (uint32_t)prow * (uint32_t)a.rowb | (k == 0 ? (uint32_t)(h - 1) | (irregular ? 16u : 0u) : 0u);
+      const bool mine = tl < ntl && ((e >= nb) | (prow + a.rpi - 1 >= lim));
+      const bool irregular = (__ballot(mine) & group_mask) != 0ull;
+      if (tl < ntl)
+        dmine[(int64_t)(first + tl) * a.ri] =
+            (uint32_t)prow * (uint32_t)a.rowb | (k == 0 ? (uint32_t)h | (irregular ? 16u : 0u) : 0u);
     }
+    first += ntl;
     start += nb;
   }
-  for (int x = 0; x < 4; ++x)
-    if (lane < a.words) drow[((int64_t)(lane / a.ri) * a.pitch + tt + x) * a.ri + lane % a.ri] = lane % a.ri == 0 ? 15u : 0u;
+  if (sub < 4) dmine[(int64_t)(first + sub) * a.ri] = k == 0 ? 15u : 0u;   // null tiles
 }
 
 hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt, uint32_t* desc, hipStream_t s) {
@@ -395,10 +410,16 @@ hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt,
   a.words = pl.desc_words;
   a.rpi = 64 / a.words;
   a.nw = 4;
+  a.lg_nw = 2;
+  a.lg_words = a.words == 16 ? 4 : 3;
   a.ri = a.words / a.nw;
   a.pitch = pl.desc_pitch;
   const int64_t rows = (int64_t)pl.B * pl.Hq * pl.nq;
-  tiles_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, s>>>(idx, cnt, desc, rows, a);
+  const size_t smem = ((size_t)pl.nk * sizeof(uint16_t) + 15) & ~(size_t)15;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tiles_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  tiles_kernel<<<(unsigned)rows, 256, smem, s>>>(idx, cnt, desc, a);
   return hipGetLastError();
 }
 

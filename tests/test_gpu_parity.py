@@ -48,6 +48,10 @@ def _case(name):
             "edge_bq96": base.with_(N=700, grid=(1, 20, 35), bq=96, bk=64, levels=3),     # rows kernel fallback
             "edge_eight_levels": base.with_(N=2048, grid=(2, 32, 32), bq=128, bk=128, levels=8),
         }[name], {}
+    if name == "bq256":           # query blocks of two 128-row workgroup slices sharing one block list and one set of tile descriptors
+        return si.small_variant(C["dit1p3b"], 1531, Hq=2, Hkv=2).with_(bq=256), {}
+    if name == "bq256_causal":    # the same, causal + grouped-query: the descriptors' visibility bound is the block's first row
+        return si.small_variant(C["vlm_prefill"], 1500, Hq=4, Hkv=2).with_(bq=256), {}
     if name == "long_rows":       # more than 4096 key blocks per row (sparse masks only: the allocation entry point refuses it)
         return si.small_variant(C["dit1p3b"], 32 * 4200 - 5, Hq=1, Hkv=1).with_(bq=32, bk=32, levels=3), {}
     if name == "f32_d128":
@@ -251,6 +255,8 @@ def _attention_case(name, over, mask=None):
     ("b32", dict(budget=0.3)),
     ("deep_d128", dict(budget=0.3)),
     ("deep_d64", dict(budget=0.2)),
+    ("bq256", dict(budget=0.3)),
+    ("bq256_causal", dict(budget=0.4)),
 ])
 def test_attention_matches_oracle_given_the_oracle_mask(name, over):
     _attention_case(name, over)
@@ -272,7 +278,7 @@ def test_degenerate_shapes_whole_path(name):
     _attention_case(name, dict(budget=0.5), mask=M)
 
 
-@pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "stress_small", "tiny", "deep_d128", "deep_d64"])
+@pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "stress_small", "tiny", "deep_d128", "deep_d64", "bq256_causal"])
 def test_attention_random_masks(name):
     """Masks no allocation rule would produce: every level everywhere, empty levels, single blocks."""
     w, _ = _case(name)
