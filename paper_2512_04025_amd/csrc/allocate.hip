@@ -340,13 +340,17 @@ hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int3
 // pooled row (block id << lg_th) | (stream position & (th - 1)) of the level's array.  A tile is
 // irregular when some row lies past the level's kept blocks, covers tokens past N, or (causal) is not
 // visible to every query row of the block.  One word per load instruction of the kernel (rpi tile
-// rows each), stored per wavefront, [row][wavefront][tile][ri]: word k of wavefront w belongs to load
-// instruction k*nw + w, and a wavefront's descriptors of consecutive tiles are adjacent in memory.  Byte offset of the instruction's first source row; the first word of
+// rows each), stored per wavefront, [row][wavefront][tile][ri]: wavefront w loads tile rows
+// 16w .. 16w+15, its word k is the instruction for rows 16w + k*rpi .., and a wavefront's descriptors
+// of consecutive tiles are adjacent in memory.  A word is the byte offset of the instruction's first
+// source row, minus the 1024*k that the instruction offset adds, plus a constant bias that keeps it
+// non-negative (the kernel's buffer descriptor starts that many bytes early).  The first word of
 // each wavefront also carries level - 1 in bits 0..3 and the irregular flag in bit 4 (row offsets are
 // multiples of 128 bytes).  Four null tiles (level field 15) follow the last one: the kernel
 // requests tiles ahead of the one it computes (and touches one cache line further: the pitch leaves room).
 struct TileArgs {
-  int N, nq, nk, bq, lg_bk, H, causal, rowb, rpi, nw, ri, words, pitch, lg_nw, lg_words;
+  int N, nq, nk, bq, lg_bk, H, causal, rowb, rpi, nw, ri, words, pitch, lg_ri, lg_words;
+  uint32_t bias;
 };
 
 __global__ __launch_bounds__(256) void tiles_kernel(const uint16_t* __restrict__ idx, const int32_t* __restrict__ cnt,
@@ -365,7 +369,7 @@ __global__ __launch_bounds__(256) void tiles_kernel(const uint16_t* __restrict__
     for (int x = tid; x < a.nk; x += 256) lst[x] = src[x];
   }
   __syncthreads();
-  const int q = tid & (a.words - 1), w = q & (a.nw - 1), k = q >> a.lg_nw;     // words, nw: powers of two
+  const int q = tid & (a.words - 1), w = q >> a.lg_ri, k = q & (a.ri - 1);     // words, ri: powers of two
   const int sub = tid >> a.lg_words, per_pass = 256 >> a.lg_words;               // tiles per pass of the workgroup
   const uint64_t group_mask = ((1ull << a.words) - 1ull) << ((lane >> a.lg_words) << a.lg_words);
   uint32_t* dmine = drow + (int64_t)w * a.pitch * a.ri + k;
@@ -393,7 +397,7 @@ __global__ __launch_bounds__(256) void tiles_kernel(const uint16_t* __restrict__
       const bool irregular = (__ballot(mine) & group_mask) != 0ull;
       if (tl < ntl)
         dmine[(int64_t)(first + tl) * a.ri] =
-            (uint32_t)prow * (uint32_t)a.rowb | (k == 0 ? (uint32_t)h | (irregular ? 16u : 0u) : 0u);
+            ((uint32_t)prow * (uint32_t)a.rowb + a.bias - 1024u * (uint32_t)k) | (k == 0 ? (uint32_t)h | (irregular ? 16u : 0u) : 0u);
     }
     first += ntl;
     start += nb;
@@ -410,9 +414,10 @@ hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt,
   a.words = pl.desc_words;
   a.rpi = 64 / a.words;
   a.nw = 4;
-  a.lg_nw = 2;
   a.lg_words = a.words == 16 ? 4 : 3;
   a.ri = a.words / a.nw;
+  a.lg_ri = a.ri == 4 ? 2 : 1;
+  a.bias = 1024u * (uint32_t)(a.ri - 1);
   a.pitch = pl.desc_pitch;
   const int64_t rows = (int64_t)pl.B * pl.Hq * pl.nq;
   const size_t smem = ((size_t)pl.nk * sizeof(uint16_t) + 15) & ~(size_t)15;

@@ -324,6 +324,21 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   auto desc_wait = [&](descv& d, descv& e) __attribute__((always_inline)) {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(d), "+s"(e), "+s"(dtouch));
   };
+  // With descriptors a wavefront loads 16 CONSECUTIVE tile rows (RPI per instruction), so the LDS
+  // destinations of its RI loads differ by 1024 bytes: that goes into the instruction offset (which
+  // moves source and destination alike; the descriptor words are biased to compensate), M0 is written
+  // once per tile, and the row offset rides in the scalar offset: no vector add per load.  The
+  // scalar offset takes part in the descriptor's range check (measured), so rows past the end of the
+  // unpadded level-1 arrays are still dropped.
+  constexpr uint32_t DBIAS = 1024u * (RI > 1 ? RI - 1 : 1);     // keeps every biased word non-negative
+  static_assert(!DESC || RPI * ROWB == 1024, "one load instruction covers 1024 bytes of LDS");
+  uint32_t klaneD[RI], vlaneD[RI];
+#pragma unroll
+  for (int k = 0; k < RI; ++k) {
+    const int r = wave * 16 + k * RPI + lrow;
+    klaneD[k] = (uint32_t)(lrow * ROWB) + (uint32_t)((lpos ^ ((r / RP256) % CPR)) << 4);
+    vlaneD[k] = (uint32_t)(lrow * ROWB) + (uint32_t)((lpos ^ (((r / RP256) % (CPR / 4)) * 4)) << 4);
+  }
   struct Stream {            // the level the K (or V) loads are currently reading from
     int lvl;                 // level - 1; 15 = null tiles; -1 = none yet
     const char* base;
@@ -334,20 +349,27 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     st.lvl = m;
     if (m == 15) { st.nrec = 0u; return; }
     const int64_t rows_h = (int64_t)a.nk << (a.lg_bk - m);
-    st.nrec = (uint32_t)(m == 0 ? (int64_t)a.N : rows_h) * (uint32_t)(D * 2);
-    if (m == 0) st.base = reinterpret_cast<const char*>((is_k ? K : V) + khead * (int64_t)a.N * D);
-    else st.base = reinterpret_cast<const char*>((is_k ? Kp : Vp) + a.lvl_off[m + 1] + khead * rows_h * D);
+    // the descriptor starts DBIAS bytes before the array and is that much longer: offsets below DBIAS never occur
+    st.nrec = (uint32_t)(m == 0 ? (int64_t)a.N : rows_h) * (uint32_t)(D * 2) + DBIAS;
+    if (m == 0) st.base = reinterpret_cast<const char*>((is_k ? K : V) + khead * (int64_t)a.N * D) - DBIAS;
+    else st.base = reinterpret_cast<const char*>((is_k ? Kp : Vp) + a.lvl_off[m + 1] + khead * rows_h * D) - DBIAS;
   };
   auto fire_desc = [&](const descv& d, Stream& st, bool is_k, int t) __attribute__((always_inline)) {
     const int m = (int)(d[0] & 15u);
     if (m != st.lvl) set_level(st, m, is_k);
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)st.base, 0, (int)st.nrec, RSRC_FLAGS);
-#pragma unroll
-    for (int k = 0; k < RI; ++k) {
-      const uint32_t off = k == 0 ? (d[0] & ~127u) : d[k % (RI == 4 ? 4 : 2)];
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(smem + (is_k ? OFF_K : OFF_V) + (t & 1) * TILEB + (k * NW + wave) * RPI * ROWB),
-                                               16, (int)(off + (is_k ? klane[k % KP] : vlane[k % KP])), 0, 0, 0);
-    }
+    lds_void* dst = (lds_void*)(smem + (is_k ? OFF_K : OFF_V) + (t & 1) * TILEB + wave * 16 * ROWB);
+    auto load = [&](auto kc) __attribute__((always_inline)) {
+      constexpr int k = decltype(kc)::value;   // (the instruction offset must be a literal)
+      if constexpr (k < RI) {
+        const uint32_t off = k == 0 ? (d[0] & ~127u) : d[k % (RI == 4 ? 4 : 2)];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 16, (int)(is_k ? klaneD[k % RI] : vlaneD[k % RI]), (int)off, 1024 * k, 0);
+      }
+    };
+    load(std::integral_constant<int, 0>{});
+    load(std::integral_constant<int, 1>{});
+    load(std::integral_constant<int, 2>{});
+    load(std::integral_constant<int, 3>{});
   };
   descv dK, dV;              // descriptors of the tile whose K rows / V rows go out next
   uint32_t meta_next = 0u;   // low bits of the descriptor of the tile whose scores are being made
