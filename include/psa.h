@@ -119,7 +119,8 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
  *   M           uint8 [B, Hq, nq, nk] (values > H are an error the kernel does not detect: undefined)
  *   O           out [B, Hq, N, d], dtype
  *   lse         nullable out, float [B, Hq, N]: natural-log softmax denominator incl. the row max
- *   scratch     workspace of psa_query_sizes' scratch_bytes (per-row level-sorted block lists)
+ *   scratch     workspace of psa_query_sizes' scratch_bytes (per-row level-sorted block lists and per-tile
+ *               load descriptors, rebuilt from M by every call)
  * bfloat16: QK^T and PV run on MFMA with fp32 accumulation, P is rounded to bfloat16 before PV.
  * float32: all arithmetic in fp32 with an accurate exp.
  * A row whose kept blocks contain no visible key produces NaN.
