@@ -242,8 +242,11 @@ struct ImpTileArgs {
 
 typedef __attribute__((address_space(3))) void imp_lds_void;
 
+// (d = 128: the LDS ring allows two workgroups per compute unit, so a wavefront may use 256 registers
+// and the MFMA accumulators stay in ordinary vector registers, readable without a copy)
 template <int D, int SWEEP>
-__global__ __launch_bounds__(256) void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 3, D == 128 ? 2 : 4)))
+void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
                                                                const bf16_t* __restrict__ Krep,
                                                                float2* __restrict__ part, float* __restrict__ S,
                                                                float* __restrict__ bmax, ImpTileArgs a) {
