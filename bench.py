@@ -236,7 +236,7 @@ def main():
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
                      "traffic": measured_traffic(w, budget, "psa::attn_mfma_kernel"),
-                     "note": "executed FLOPs / mean HIP-event time of psa_attention_fwd (includes its block-list kernel)"},
+                     "note": "executed FLOPs / mean HIP-event time of psa_attention_fwd (includes its block-list and tile-descriptor kernels)"},
         "roofline_pyramid": None if pyr_gbs is None else {
             "kernel": "pyramid_kernel", "bound": "hbm", "achieved": pyr_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": measured_traffic(w, budget, "psa::pyramid_kernel"),
