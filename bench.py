@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="dit1p3b", help="key of synth_inputs.CONFIGS")
     ap.add_argument("--budget", type=float, default=None, help="compute budget rho-bar (default: the workload's)")
     ap.add_argument("--levels", type=int, default=None, help="pyramid depth override (1 = binary block-sparse)")
