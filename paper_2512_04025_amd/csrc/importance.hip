@@ -242,15 +242,18 @@ struct ImpTileArgs {
 
 typedef __attribute__((address_space(3))) void imp_lds_void;
 
-// (d = 128: the LDS ring allows two workgroups per compute unit, so a wavefront may use 256 registers
-// and the MFMA accumulators stay in ordinary vector registers, readable without a copy)
+// Sweep 1 runs with a ring of three tiles and no staging buffer: 48 KB of LDS at d = 128, three
+// workgroups per compute unit.  Sweep 2 (ring of four + staged scores, 72 KB) fits two, so there a
+// wavefront may use 256 registers.  Either way the MFMA accumulators stay in ordinary vector
+// registers, readable without a copy.
 template <int D, int SWEEP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 128 ? 2 : 3, D == 128 ? 2 : 4)))
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu(SWEEP == 1 || D == 64 ? 3 : 2, SWEEP == 1 ? 3 : (D == 128 ? 2 : 4))))
 void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
                                                                const bf16_t* __restrict__ Krep,
                                                                float2* __restrict__ part, float* __restrict__ S,
                                                                float* __restrict__ bmax, ImpTileArgs a) {
-  constexpr int SQ = 8, SK = 8, KS = D / 16, BN = 64, NW = 4, NSLOT = 4;
+  constexpr int SQ = 8, SK = 8, KS = D / 16, BN = 64, NW = 4, NSLOT = SWEEP == 1 ? 3 : 4;
   constexpr int CPR = D / 8, RPI = 64 / CPR, NINST = BN / RPI, RI = NINST / NW, RP256 = 16 / CPR;
   constexpr int ROWB = D * 2, TILEB = BN * ROWB;
   constexpr int KP = 16 / (NW * RPI) > 1 ? 16 / (NW * RPI) : 1;
@@ -562,17 +565,36 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
     asm volatile("s_barrier" ::: "memory");
   };
 
-  // Tile t has landed once at most the loads issued after its own are outstanding: those of tiles
-  // t+1 and t+2 (RI each).  (Sweep 2 writes S in batches, after a full wait, so stores never sit
-  // between the loads being counted.)
+  // Tile t has landed once at most the memory operations issued after its own loads are outstanding
+  // (loads and stores leave the counter in order): the loads of the tiles t+1 .. t+NSLOT-2 that exist
+  // (RI each) and, in sweep 1 with block maxima, one store for each of the tiles t-(NSLOT-1) .. t-1
+  // that exist (tile t was requested in the step of tile t-(NSLOT-1), before that step's store).
+  // The count must be exact or low: a high count would let the wavefront through early.  (Sweep 2
+  // writes S in batches, after a full wait, so stores never sit between the loads being counted.)
   auto wait_tile = [&](int t) __attribute__((always_inline)) {
-    constexpr int G = RI, WITH_STORES = 2 * RI + 3;    // sweep 1 keeping block maxima: one store per tile, three tiles back
-    if (SWEEP == 2 && t % STAGE_TILES < 3) __builtin_amdgcn_s_waitcnt(0x0F70);   // stores of the last write-out may be in flight
-    else if (SWEEP == 1 && bmax && t >= 3 && t + 2 < nt)
-      __builtin_amdgcn_s_waitcnt((WITH_STORES & 15) | ((WITH_STORES >> 4) << 14) | 0x0F70);
-    else if (t + 2 < nt) __builtin_amdgcn_s_waitcnt(((2 * G) & 15) | (((2 * G) >> 4) << 14) | 0x0F70);
-    else if (t + 1 < nt) __builtin_amdgcn_s_waitcnt((G & 15) | ((G >> 4) << 14) | 0x0F70);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (SWEEP == 2 && t % STAGE_TILES < 3) { __builtin_amdgcn_s_waitcnt(0x0F70); return; }   // stores of the last write-out may be in flight
+    const int ahead = nt - 1 - t < NSLOT - 2 ? nt - 1 - t : NSLOT - 2;
+    const int stores = SWEEP == 1 && bmax ? (t < NSLOT - 1 ? t : NSLOT - 1) : 0;
+    const int cnt = ahead * RI + stores;
+    auto wait = [&](auto c) __attribute__((always_inline)) {
+      constexpr int C = decltype(c)::value;
+      __builtin_amdgcn_s_waitcnt((C & 15) | ((C >> 4) << 14) | 0x0F70);
+    };
+    static_assert((NSLOT - 2) * RI + NSLOT - 1 <= 11, "cases below");
+    switch (cnt) {
+      case 0: wait(std::integral_constant<int, 0>{}); break;
+      case 1: wait(std::integral_constant<int, 1>{}); break;
+      case 2: wait(std::integral_constant<int, 2>{}); break;
+      case 3: wait(std::integral_constant<int, 3>{}); break;
+      case 4: wait(std::integral_constant<int, 4>{}); break;
+      case 5: wait(std::integral_constant<int, 5>{}); break;
+      case 6: wait(std::integral_constant<int, 6>{}); break;
+      case 7: wait(std::integral_constant<int, 7>{}); break;
+      case 8: wait(std::integral_constant<int, 8>{}); break;
+      case 9: wait(std::integral_constant<int, 9>{}); break;
+      case 10: wait(std::integral_constant<int, 10>{}); break;
+      default: wait(std::integral_constant<int, 11>{}); break;
+    }
   };
   auto one = [&](auto slot_tag, int t) __attribute__((always_inline)) {
     wait_tile(t);
@@ -585,7 +607,9 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
     one(std::integral_constant<int, 0>{}, t);
     if (t + 1 < nt) one(std::integral_constant<int, 1>{}, t + 1);
     if (t + 2 < nt) one(std::integral_constant<int, 2>{}, t + 2);
-    if (t + 3 < nt) one(std::integral_constant<int, 3>{}, t + 3);
+    if constexpr (NSLOT == 4) {
+      if (t + 3 < nt) one(std::integral_constant<int, 3>{}, t + 3);
+    }
   }
 
   if (SWEEP == 2 && nt < nt_slice) {           // key blocks of the slice that no row of this workgroup sees: score 0
@@ -646,8 +670,9 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
   const int ntile_all = (pl.nk * 8 + 63) / 64;
   // Key slices: the workgroups run in rounds of `slots` (what fits on the chip at once); pick the
   // slice count with the least rounds x work-per-workgroup, preferring fewer slices on a tie.
-  const int smem = 4 * 64 * D * 2 + 16 * 8 * 16 * (int)sizeof(float);   // ring of 4 tiles + staged scores
-  const int per_cu = 160 * 1024 / smem < 3 ? 160 * 1024 / smem : 3;
+  const int smem = 4 * 64 * D * 2 + 16 * 8 * 16 * (int)sizeof(float);   // sweep 2: ring of 4 tiles + staged scores
+  const int smem1 = 3 * 64 * D * 2;                                      // sweep 1: ring of 3 tiles
+  const int per_cu = 160 * 1024 / smem1 < 3 ? 160 * 1024 / smem1 : 3;
   const int slots = 256 * per_cu;
   const int base = row_groups * pl.Hq * pl.B;
   int ksplit = 1;
@@ -661,14 +686,14 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
   dim3 grid(row_groups, ksplit, pl.Hq * pl.B);
   auto k1 = importance_tiles_kernel<D, 1>;
   auto k2 = importance_tiles_kernel<D, 2>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, smem1);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (e != hipSuccess) return e;
   const bool keep_max = pl.est_pool == PSA_EST_MAX;
   a.bm_rows = row_groups * 128;
   a.bm_pitch = ntile_all * 8;
-  k1<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S,
+  k1<<<grid, 256, smem1, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S,
                              keep_max ? bmax : nullptr, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
