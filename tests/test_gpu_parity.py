@@ -195,6 +195,30 @@ def test_level_map_from_identical_scores_is_bit_exact(name, over):
     np.testing.assert_allclose(r.buf.rho.cpu().numpy(), orc.compute_ratio(got, r.op), rtol=1e-6)
 
 
+@pytest.mark.parametrize("nk", [40, 100, 200, 700, 1500, 3000, 4096])
+def test_level_map_every_sort_width(nk):
+    """Rows of 40 ... 4096 key blocks: one case for every width of the allocation kernel's register
+    sort (64, 128, ... 4096 keys per row), scores given, quota and threshold rules, with and without
+    the causal mask."""
+    import torch
+    w = si.small_variant(si.CONFIGS["dit1p3b"], nk * 32 - 7, Hq=1, Hkv=1).with_(bq=1024, bk=32, levels=3)
+    rng = np.random.default_rng(nk)
+    for over in (dict(budget=0.3), dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.9)), dict(budget=0.2, causal=True)):
+        causal = over.pop("causal", False)
+        op = oracle_params(w.with_(causal=causal), **over)
+        gp = gpu_params(op)
+        assert op.nk == nk
+        buf = Buffers(gp)
+        S = (rng.random((op.B, op.Hq, op.nq, op.nk)) ** 6).astype(np.float32)
+        S[0, 0, 0, : nk // 2] = S[0, 0, 0, nk - nk // 2:]                  # equal scores: order decided by block index
+        ref = orc.allocate_levels(S, op)
+        psa.psa_allocate_levels(gp, None, None, None, buf.M, buf.scratch, scores_in=torch.from_numpy(S).cuda(), rho_out=buf.rho)
+        torch.cuda.synchronize()
+        got = buf.M.cpu().numpy()
+        _check_level_map(got, ref, S, op)
+        np.testing.assert_allclose(buf.rho.cpu().numpy(), orc.compute_ratio(got, op), rtol=1e-6)
+
+
 def test_level_map_edge_rows_and_cap():
     """One-hot, all-zero and constant rows; per-block level cap (App. B.1)."""
     import torch
