@@ -52,6 +52,8 @@ def _case(name):
         return si.small_variant(C["dit1p3b"], 1531, Hq=2, Hkv=2).with_(bq=256), {}
     if name == "bq256_causal":    # the same, causal + grouped-query: the descriptors' visibility bound is the block's first row
         return si.small_variant(C["vlm_prefill"], 1500, Hq=4, Hkv=2).with_(bq=256), {}
+    if name.startswith("wide_"):  # rows of int(name[5:]) key blocks of 32 tokens, full 128-row workgroups, sparse caller-made masks
+        return si.small_variant(C["dit1p3b"], int(name[5:]) * 32 - 5, Hq=1, Hkv=1).with_(bq=128, bk=32, levels=3), {}
     if name == "long_rows":       # more than 4096 key blocks per row (sparse masks only: the allocation entry point refuses it)
         return si.small_variant(C["dit1p3b"], 32 * 4200 - 5, Hq=1, Hkv=1).with_(bq=32, bk=32, levels=3), {}
     if name == "f32_d128":
@@ -333,6 +335,26 @@ def test_attention_rows_longer_than_the_allocation_limit():
     M[0, 0, 7] = 0
     M[0, 0, 7, op.nk - 1] = 3                                        # only the last, partial block, coarsest level
     _attention_case("long_rows", {}, mask=M)
+
+
+@pytest.mark.parametrize("nk", [100, 200, 3000])
+def test_attention_wide_rows_sparse_masks(nk):
+    """Block lists and tile descriptors of rows with 100 ... 3000 key blocks (the list builder keeps a
+    row in 2, 4 ... 64 registers per lane), a handful of kept blocks per row at random levels."""
+    w, _ = _case(f"wide_{nk}")
+    op = oracle_params(w)
+    assert op.nk == nk
+    rng = np.random.default_rng(nk)
+    M = np.zeros((op.B, op.Hq, op.nq, op.nk), dtype=np.uint8)
+    for i in range(op.nq):
+        cols = rng.choice(op.nk, size=9, replace=False)
+        M[0, 0, i, cols] = rng.integers(1, op.levels + 1, size=9)
+    M[..., 0] = 1
+    M[0, 0, 1] = 0
+    M[0, 0, 1, op.nk - 1] = op.levels                                # only the last, partial block, coarsest level
+    M[0, 0, 2] = 0
+    M[0, 0, 2, op.nk - 2:] = 2                                       # one tile of two adjacent level-2 blocks, the second partial
+    _attention_case(f"wide_{nk}", {}, mask=M)
 
 
 def test_all_level1_mask_equals_dense_ref():
