@@ -84,7 +84,9 @@ def measured_traffic(w, budget, kernel_prefix: str):
 
 def attainable_peaks(torch, psa):
     """What this GPU sustains on two trivial kernels of the library: a streaming copy (read + write
-    bytes per second) and a loop of nothing but bf16 32x32x16 MFMAs on register operands."""
+    bytes per second) and a loop of nothing but bf16 32x32x16 MFMAs on register operands, once with
+    few-valued operands and once with random signs and mantissas (the clock follows the power the
+    multipliers draw, so the second is the ceiling for real activations)."""
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
@@ -97,16 +99,20 @@ def attainable_peaks(torch, psa):
     e1.record()
     torch.cuda.synchronize()
     copy_gbs = 5 * 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    psa.psa_probe_mfma(sink, 2048, 2000)
-    e0.record()
-    flops = 0.0
-    for _ in range(5):
-        flops += psa.psa_probe_mfma(sink, 2048, 2000)
-    e1.record()
-    torch.cuda.synchronize()
-    mfma_tflops = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
-    return {"hbm_copy_gbs": copy_gbs, "mfma_bf16_tflops": mfma_tflops,
-            "note": "measured on this GPU by psa_probe_copy (1 GiB) and psa_probe_mfma (2048 workgroups x 2000 x 16 MFMAs per wavefront)"}
+    rates = {}
+    for random_operands in (False, True):
+        for _ in range(3):     # long enough for the clock to settle
+            psa.psa_probe_mfma(sink, 2048, 2000, random_operands)
+        e0.record()
+        flops = 0.0
+        for _ in range(5):
+            flops += psa.psa_probe_mfma(sink, 2048, 2000, random_operands)
+        e1.record()
+        torch.cuda.synchronize()
+        rates[random_operands] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return {"hbm_copy_gbs": copy_gbs, "mfma_bf16_tflops": rates[False], "mfma_bf16_tflops_random_operands": rates[True],
+            "note": "measured on this GPU by psa_probe_copy (1 GiB) and psa_probe_mfma (2048 workgroups x 2000 x 16 MFMAs "
+                    "per wavefront; few-valued operands, then random signs and mantissas)"}
 
 
 def cpu_baseline(w, budget, Q, K, V, n_heads: int = 3):
@@ -246,6 +252,7 @@ def main():
         att = attainable_peaks(torch, psa)
         out["attainable"] = att
         out["roofline"]["frac_of_attainable"] = attn_tflops / att["mfma_bf16_tflops"]
+        out["roofline"]["frac_of_attainable_random_operands"] = attn_tflops / att["mfma_bf16_tflops_random_operands"]
         if pyr_gbs is not None:
             out["roofline_pyramid"]["frac_of_attainable"] = pyr_gbs / att["hbm_copy_gbs"]
     if w.dtype != "bf16":

@@ -65,7 +65,7 @@ def load_library() -> ctypes.CDLL:
     lib.psa_attention_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_dense_ref.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.psa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
-    lib.psa_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
+    lib.psa_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
     for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd",
@@ -150,9 +150,10 @@ def psa_probe_copy(src, dst, nbytes: int, stream=None) -> None:
            "psa_probe_copy")
 
 
-def psa_probe_mfma(sink, workgroups: int, iters: int, stream=None) -> float:
+def psa_probe_mfma(sink, workgroups: int, iters: int, random_operands: bool = False, stream=None) -> float:
     """Launches the MFMA-only loop; returns the floating-point operations of the launch."""
     flops = ctypes.c_double(0.0)
     _check(load_library().psa_probe_mfma(_ptr(sink), ctypes.c_int(workgroups), ctypes.c_int(iters),
-                                         ctypes.byref(flops), _stream(stream)), "psa_probe_mfma")
+                                         ctypes.c_int(1 if random_operands else 0), ctypes.byref(flops),
+                                         _stream(stream)), "psa_probe_mfma")
     return flops.value

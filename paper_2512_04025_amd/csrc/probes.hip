@@ -13,8 +13,17 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
 // Every wavefront issues iters x 16 independent-enough 32x32x16 MFMAs (4 accumulators); operands are
-// registers, there is no memory traffic besides one store per lane at the end.
+// registers, there is no memory traffic besides one store per lane at the end.  The rate depends on
+// the operand DATA: with random signs and mantissas (values in +-[0.5, 2), like real activations)
+// the multipliers toggle far more, the chip draws more power and clocks lower than with the
+// few-valued operands of RANDOM = false.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters) {
   const int lane = threadIdx.x & 63;
   f32x16 acc[4];
@@ -22,15 +31,31 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sin
   for (int j = 0; j < 4; ++j)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-  bf16x8 a, b;
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (__bf16)(float)((lane + e) & 3);
-    b[e] = (__bf16)(1.0f / 64.0f);
+  for (int j = 0; j < 4; ++j) {
+    if (RANDOM) {
+      u32x4 ua, ub;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t h = probe_hash(threadIdx.x * 64u + blockIdx.x * 7919u + j * 16u + e), g = probe_hash(h + 12345u);
+        ua[e] = (h & 0x80ff80ffu) | 0x3f003f00u;   // two bfloat16: random sign and 7 mantissa bits, exponent of 0.5 or 1
+        ub[e] = (g & 0x80ff80ffu) | 0x3f003f00u;
+      }
+      a[j] = __builtin_bit_cast(bf16x8, ua);
+      b[j] = __builtin_bit_cast(bf16x8, ub);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        a[j][e] = (__bf16)(float)((lane + e) & 3);
+        b[j][e] = (__bf16)(1.0f / 64.0f);
+      }
+    }
   }
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j & 3], 0, 0, 0);
+    for (int j = 0; j < 16; ++j)
+      acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j & 3], b[(j >> 2) & 3], acc[j & 3], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -49,9 +74,11 @@ extern "C" int psa_probe_copy(const void* src, void* dst, size_t bytes, void* st
   return hipGetLastError() == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 
-extern "C" int psa_probe_mfma(float* sink, int workgroups, int iters, double* flops, void* stream) {
+extern "C" int psa_probe_mfma(float* sink, int workgroups, int iters, int random_operands, double* flops,
+                              void* stream) {
   if (!sink || workgroups <= 0 || iters <= 0) return PSA_EINVAL;
-  psa::probe_mfma_kernel<<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(sink, iters);
+  if (random_operands) psa::probe_mfma_kernel<true><<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(sink, iters);
+  else psa::probe_mfma_kernel<false><<<workgroups, 256, 0, static_cast<hipStream_t>(stream)>>>(sink, iters);
   if (flops) *flops = (double)workgroups * 4.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
   return hipGetLastError() == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
