@@ -142,7 +142,8 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
     total_tiles += ((nb << lg_th) + BN - 1) >> LG_BN;
   }
   for (int x = tid; x < total_blocks; x += NT) list[x] = my_idx[x];
-  {  // tile buffers start as zeros: a lane whose source row is out of range leaves its LDS slot alone
+  {  // tile buffers start as zeros (a lane whose source row is out of range was seen to store zeros, but
+     // nothing here relies on that: an out-of-range row may as well keep what its slot held)
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (int x = tid * 16; x < 4 * TILEB; x += NT * 16) *reinterpret_cast<u32x4*>(smem + x) = z;
   }

@@ -306,7 +306,8 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
     while (nt > 0 && key_pos((t_lo + nt - 1) * BN) > qpos_max) --nt;
   }
 
-  {  // ring starts as zeros: a lane whose key row is out of range leaves its LDS slot alone
+  {  // ring starts as zeros (a lane whose key row is out of range was seen to store zeros, but nothing here
+     // relies on that: an out-of-range row may as well keep what its slot held)
     const u32x4 z = {0u, 0u, 0u, 0u};
     for (int x = tid * 16; x < NSLOT * TILEB; x += 256 * 16) *reinterpret_cast<u32x4*>(ring + x) = z;
   }
