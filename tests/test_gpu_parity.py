@@ -514,3 +514,23 @@ def test_pyramid_levels_beat_binary_mask_at_equal_budget():
             errs[(levels, budget)] = rel_l2(out, dense)
     assert errs[(5, 0.1)] < errs[(1, 0.1)] and errs[(5, 0.3)] < errs[(1, 0.3)]
     assert errs[(5, 0.3)] < errs[(5, 0.1)] and errs[(1, 0.3)] < errs[(1, 0.1)]
+
+
+# ------------------------------------------------------------------------------- measurement aids
+def test_measurement_probes_run():
+    """The two measurement aids of the library: the copy moves the bytes, the MFMA loop reports its
+    floating-point operations for both kinds of operands and leaves finite sums."""
+    import torch
+    n = 1 << 22
+    src = torch.arange(n, dtype=torch.int32, device="cuda").view(torch.uint8)
+    dst = torch.zeros_like(src)
+    psa.psa_probe_copy(src, dst, src.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    sink = torch.empty(8 * 256, dtype=torch.float32, device="cuda")
+    for random_operands in (False, True):
+        sink.fill_(float("nan"))
+        flops = psa.psa_probe_mfma(sink, 8, 3, random_operands)
+        torch.cuda.synchronize()
+        assert flops == 8 * 4 * 3 * 16 * 2.0 * 32 * 32 * 16
+        assert bool(torch.isfinite(sink).all())
