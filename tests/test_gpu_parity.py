@@ -242,9 +242,14 @@ def test_level_map_edge_rows_and_cap():
 
 
 # ------------------------------------------------------------------------------- attention
-def _attention_case(name, over, mask=None):
+def _attention_case(name, over, mask=None, q_exponent_shift=0):
     import torch
     r = Run(name, **over)
+    if q_exponent_shift:          # Q times 2^shift, exactly (bfloat16 bit patterns: the exponent field moves)
+        assert r.w.dtype == "bf16"
+        Q, _, _ = si.generate_qkv(r.w)
+        Q = np.where((Q & 0x7f80) != 0, Q + np.uint16(q_exponent_shift << 7), Q).astype(np.uint16)
+        r.Q64, r.Qd = si.to_f64(Q, r.w.dtype), to_dev(Q, r.w.dtype)
     Kp, Vp = r.pyramids()
     if mask is None:
         mask = orc.allocate_levels(orc.importance(r.Q64, r.K64, r.op), r.op)
@@ -286,6 +291,13 @@ def _attention_case(name, over, mask=None):
 ])
 def test_attention_matches_oracle_given_the_oracle_mask(name, over):
     _attention_case(name, over)
+
+
+@pytest.mark.parametrize("name,over", [("dit_small", dict(budget=0.3)), ("vlm_small", dict(budget=0.4)), ("stress_small", dict(budget=0.3))])
+def test_attention_wide_range_of_logits(name, over):
+    """Queries scaled by 8: the logits of a row span hundreds of binary orders of magnitude, the running
+    maximum moves by more than the lazy-rescale margin again and again and most probabilities underflow."""
+    _attention_case(name, over, q_exponent_shift=3)
 
 
 @pytest.mark.parametrize("name", ["edge_one_partial_block", "edge_n8", "edge_single_level", "edge_causal_tiny",
