@@ -53,6 +53,23 @@ __device__ __forceinline__ double wave_incl_scan(double x, int lane) {
   return x;
 }
 
+// Value of lane (l ^ m) for m = 1, 2, 4 ... 32.  Neighbours at distance 1 and 2 come through the data-parallel
+// primitives of the vector unit (no LDS instruction, no wait), 4, 8 and 16 through the LDS crossbar's
+// swizzle (no address register), 32 through a permute.
+__device__ __forceinline__ uint32_t lane_xor32(uint32_t v, int m) {
+  switch (m) {
+    case 1: return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    case 2: return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    case 4: return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (4 << 10));               // and 0x1f, or 0, xor 4
+    case 8: return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (8 << 10));
+    case 16: return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (16 << 10));
+    default: return (uint32_t)__shfl_xor((int)v, 32, 64);
+  }
+}
+__device__ __forceinline__ uint64_t lane_xor64(uint64_t v, int m) {
+  return ((uint64_t)lane_xor32((uint32_t)(v >> 32), m) << 32) | lane_xor32((uint32_t)v, m);
+}
+
 // One wavefront per query block, the whole row in registers: lane l holds the KPL keys at sorted
 // positions l*KPL .. l*KPL+KPL-1.  Bitonic stages whose partner distance is below KPL exchange
 // registers of one lane (register numbers are compile-time); longer distances exchange the same
@@ -111,14 +128,16 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
       }
     }
   }
+#pragma unroll
   for (int kl = 2; kl <= 64; kl <<= 1) {      // phase k = kl * KPL
     const bool up = (lane & kl) == 0;
+#pragma unroll
     for (int m = kl >> 1; m > 0; m >>= 1) {   // partner lane l ^ m
       const bool keep_min = ((lane & m) == 0) == up;
 #pragma unroll
       for (int r = 0; r < KPL; ++r) {
         const uint64_t mine = key[r];
-        const uint64_t other = __shfl_xor((unsigned long long)mine, m, 64);
+        const uint64_t other = lane_xor64(mine, m);
         key[r] = ((mine < other) == keep_min) ? mine : other;
       }
     }
