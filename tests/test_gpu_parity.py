@@ -427,6 +427,52 @@ def test_calls_are_deterministic():
     assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
 
 
+def test_whole_path_replays_from_a_captured_graph():
+    """The three calls recorded into one HIP graph (they allocate nothing, never synchronise and record
+    no memset nodes) and replayed with new inputs give what the eager calls give; eager work and
+    synchronisations sit between the replays."""
+    import torch
+    r = Run("dit_small", budget=0.2)
+    b = r.buf
+
+    def forward():
+        psa.psa_build_pyramid(r.gp, r.Kd, r.Vd, b.Kpyr, b.Vpyr)
+        psa.psa_allocate_levels(r.gp, r.Qd, r.Kd, b.Kpyr, b.M, b.scratch, rho_out=b.rho)
+        psa.psa_attention_fwd(r.gp, r.Qd, r.Kd, r.Vd, b.Kpyr, b.Vpyr, b.M, b.O, b.scratch)
+
+    forward()
+    torch.cuda.synchronize()
+    eager = (b.M.clone(), b.O.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        forward()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        forward()
+    q0, k0 = r.Qd.clone(), r.Kd.clone()
+    for it in range(3):
+        b.O.fill_(float("nan"))
+        b.M.fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(b.M, eager[0]), it
+        assert torch.equal(b.O.view(torch.int16), eager[1].view(torch.int16)), it
+        (b.O.float().sum() + b.M.float().sum()).item()      # eager work between the replays
+    # new inputs in the same buffers: the replay follows them
+    r.Qd.copy_(torch.roll(q0, 1, dims=2))
+    r.Kd.copy_(torch.roll(k0, 1, dims=2))
+    graph.replay()
+    torch.cuda.synchronize()
+    replayed = (b.M.clone(), b.O.clone())
+    forward()
+    torch.cuda.synchronize()
+    assert torch.equal(b.M, replayed[0])
+    assert torch.equal(b.O.view(torch.int16), replayed[1].view(torch.int16))
+    assert not torch.equal(b.O.view(torch.int16), eager[1].view(torch.int16))
+
+
 # ------------------------------------------------------------------------------- full benchmark sizes
 def _full_workload(key):
     """Benchmark-size workloads; the two largest keep their full sequence length, block sizes and
