@@ -473,6 +473,36 @@ def test_whole_path_replays_from_a_captured_graph():
     assert not torch.equal(b.O.view(torch.int16), eager[1].view(torch.int16))
 
 
+def test_two_streams_with_their_own_buffers_do_not_interfere():
+    """Two different problems issued back to back on two streams (each with its own outputs and scratch)
+    give what each gives alone: the library keeps no state between or across calls."""
+    import torch
+    runs = [Run("dit_small", budget=0.2), Run("vlm_small", budget=0.25)]
+
+    def forward(r, stream=None):
+        b = r.buf
+        psa.psa_build_pyramid(r.gp, r.Kd, r.Vd, b.Kpyr, b.Vpyr, stream=stream)
+        psa.psa_allocate_levels(r.gp, r.Qd, r.Kd, b.Kpyr, b.M, b.scratch, stream=stream)
+        psa.psa_attention_fwd(r.gp, r.Qd, r.Kd, r.Vd, b.Kpyr, b.Vpyr, b.M, b.O, b.scratch, stream=stream)
+
+    alone = []
+    for r in runs:
+        forward(r)
+        torch.cuda.synchronize()
+        alone.append((r.buf.M.clone(), r.buf.O.clone()))
+        r.buf.O.fill_(float("nan"))
+        r.buf.M.fill_(0)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for _ in range(3):
+        for r, st in zip(runs, streams):
+            forward(r, st)
+    torch.cuda.synchronize()
+    for r, (M, O) in zip(runs, alone):
+        assert torch.equal(r.buf.M, M)
+        assert torch.equal(r.buf.O.view(torch.int16), O.view(torch.int16))
+
+
 # ------------------------------------------------------------------------------- full benchmark sizes
 def _full_workload(key):
     """Benchmark-size workloads; the two largest keep their full sequence length, block sizes and
