@@ -11,7 +11,7 @@ in the docstring (the full list of readings lives in the repository's design not
 Pins (see tests/test_oracle_pins.py): dense attention vs. an element-wise brute force; the pyramid
 vs. the recursive 2:1 pooling of Eq. 2-3; PSA with M == 1 vs. dense; PSA on keys constant inside
 every pooling group vs. dense restricted to the kept blocks (catches a missing/wrong (h-1) ln 2);
-Alg. 1's online recurrence vs. the closed-form softmax over the gathered pooled keys; importance
+the one-softmax form of Eq. 8 vs. Alg. 1's online recurrence; importance
 with s_q = b_q, s_k = b_k vs. block-max / block-mean of the brute-force attention matrix; Alg. 2 on
 hand-computed rows; Eq. 9 on the printed preset table (Table 9).  No function here is unpinned
 against the paper's definitions; end-to-end *quality* on real model activations is unpinned (the
@@ -366,11 +366,14 @@ def _block_logits(Qi: np.ndarray, rows: np.ndarray, Kh: np.ndarray, j: int, h: i
 
 def psa_attention(Q: np.ndarray, Kp: Dict[int, np.ndarray], Vp: Dict[int, np.ndarray], M: np.ndarray,
                   p: Params, q_blocks: Optional[Iterable[int]] = None, heads: Optional[Iterable[Tuple[int, int]]] = None):
-    """Adaptive pyramid attention, Alg. 1, as printed: per query block, key blocks in ascending
-    order, online-softmax state (o, m, l) per row, O = o / l.
+    """Adaptive pyramid attention as Eq. 8 defines its result: for every query row, ONE softmax over
+    the logits of all kept pooled keys (each carrying its bias ln c, c = tokens under the key:
+    (h-1) ln 2 for a full level-h key), then the weighted mean of the pooled values.  The online
+    recurrence of Alg. 1 reaches the same numbers block by block (psa_attention_online; pinned equal).
 
     Q [B,Hq,N,d] fp64; Kp/Vp from build_pyramid; M [B,Hq,nq,nk].  Returns (O [B,Hq,N,d] fp64,
-    lse [B,Hq,N]); rows of query blocks not in q_blocks (or heads not listed) are left NaN.
+    lse [B,Hq,N] = log of the softmax denominator); rows of query blocks not in q_blocks (or heads
+    not listed) are left NaN.
     """
     group = p.Hq // p.Hkv
     O = np.full((p.B, p.Hq, p.N, p.d), np.nan)
@@ -382,43 +385,48 @@ def psa_attention(Q: np.ndarray, Kp: Dict[int, np.ndarray], Vp: Dict[int, np.nda
         for i in qb:
             rows = np.arange(i * p.bq, min((i + 1) * p.bq, p.N))
             Qi = Q[b, hq, rows]
-            o = np.zeros((rows.size, p.d))
-            m = np.full(rows.size, -np.inf)
-            l = np.zeros(rows.size)
+            logits, vals = [], []
             for j in range(p.nk):
                 h = int(M[b, hq, i, j])
-                if h == 0:
-                    continue
-                s, idx = _block_logits(Qi, rows, Kp[h][b, hk], j, h, p)
-                m_new = np.maximum(s.max(axis=1), m)
-                m_safe = np.where(np.isfinite(m_new), m_new, 0.0)
-                P = np.exp(s - m_safe[:, None])
-                alpha = np.exp(np.where(np.isfinite(m), m, -np.inf) - m_safe)
-                l = l * alpha + P.sum(axis=1)
-                o = o * alpha[:, None] + P @ Vp[h][b, hk][idx]
-                m = m_new
-            O[b, hq, rows] = o / l[:, None]
-            LSE[b, hq, rows] = m + np.log(l)
+                if h:
+                    s, idx = _block_logits(Qi, rows, Kp[h][b, hk], j, h, p)
+                    logits.append(s)
+                    vals.append(Vp[h][b, hk][idx])
+            if not logits:
+                continue
+            s = np.concatenate(logits, axis=1)
+            v = np.concatenate(vals, axis=0)
+            mx = s.max(axis=1, keepdims=True)
+            w = np.exp(s - np.where(np.isfinite(mx), mx, 0.0))
+            l = w.sum(axis=1, keepdims=True)
+            O[b, hq, rows] = (w @ v) / l
+            LSE[b, hq, rows] = (mx + np.log(l))[:, 0]
     return O, LSE
 
 
-def psa_attention_closed_form(Q, Kp, Vp, M, p: Params, b: int, hq: int, i: int) -> np.ndarray:
-    """Eq. 8 written out for one query block: one softmax over the logits of all kept pooled keys
-    (bias included), then the weighted mean of the pooled values.  Used to pin the recurrence."""
+def psa_attention_online(Q, Kp, Vp, M, p: Params, b: int, hq: int, i: int) -> np.ndarray:
+    """Alg. 1 for one query block: key blocks in ascending order, running state (o, m, l) per row,
+    rescaled whenever the running maximum moves, O = o / l.  Secondary: pins that the recurrence and
+    the one-softmax form of Eq. 8 agree."""
     hk = hq // (p.Hq // p.Hkv)
     rows = np.arange(i * p.bq, min((i + 1) * p.bq, p.N))
     Qi = Q[b, hq, rows]
-    logits, vals = [], []
+    o = np.zeros((rows.size, p.d))
+    m = np.full(rows.size, -np.inf)
+    l = np.zeros(rows.size)
     for j in range(p.nk):
         h = int(M[b, hq, i, j])
-        if h:
-            s, idx = _block_logits(Qi, rows, Kp[h][b, hk], j, h, p)
-            logits.append(s)
-            vals.append(Vp[h][b, hk][idx])
-    s = np.concatenate(logits, axis=1)
-    v = np.concatenate(vals, axis=0)
-    w = np.exp(s - s.max(axis=1, keepdims=True))
-    return (w @ v) / w.sum(axis=1, keepdims=True)
+        if h == 0:
+            continue
+        s, idx = _block_logits(Qi, rows, Kp[h][b, hk], j, h, p)
+        m_new = np.maximum(m, s.max(axis=1))
+        ref = np.where(np.isfinite(m_new), m_new, 0.0)
+        alpha = np.exp(m - ref)                    # exp(-inf) = 0 while nothing has been seen
+        P = np.exp(s - ref[:, None])
+        l = alpha * l + P.sum(axis=1)
+        o = alpha[:, None] * o + P @ Vp[h][b, hk][idx]
+        m = m_new
+    return o / l[:, None]
 
 
 # --------------------------------------------------------------------------- Eq. 1: dense attention

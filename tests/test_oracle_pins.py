@@ -206,8 +206,8 @@ def test_online_recurrence_equals_closed_form(causal):
     O, _ = orc.psa_attention(Q, Kp, Vp, M, p)
     for h in range(p.Hq):
         for i in range(p.nq):
-            cf = orc.psa_attention_closed_form(Q, Kp, Vp, M, p, 0, h, i)
-            np.testing.assert_allclose(O[0, h, i * p.bq:(i + 1) * p.bq], cf, rtol=1e-11, atol=1e-12)
+            rec = orc.psa_attention_online(Q, Kp, Vp, M, p, 0, h, i)
+            np.testing.assert_allclose(O[0, h, i * p.bq:(i + 1) * p.bq], rec, rtol=1e-11, atol=1e-12)
 
 
 def test_binary_levels_equal_block_sparse_attention():
@@ -432,3 +432,23 @@ def test_error_shrinks_with_budget_and_pyramid_beats_binary():
     assert e100 < 1e-12 and r100 == 1.0
     assert e50 < e25
     assert r25 <= rb + 1e-12 and e25 < b25                              # no more FLOPs, smaller error
+
+
+# ---------------------------------------------------------------- executed FLOPs of Alg. 1 (roofline numerator)
+def test_executed_flops_hand_computed_with_ragged_tail():
+    """N = 19, b_q = b_k = 8, H = 2, d = 4.  Query blocks hold 8, 8, 3 rows; key blocks hold 8, 8, 3
+    tokens at level 1 and 4, 4, 2 pooled tokens at level 2 (tokens 16-17 and the lone token 18).
+    M = [[1,2,0],[0,1,2],[2,0,1]]: 8*(8+4) + 8*(8+2) + 3*(4+3) = 197 row-token pairs, 4 d FLOPs each."""
+    p = Params(1, 1, 1, 19, 4, 8, 8, 2)
+    M = np.array([[1, 2, 0], [0, 1, 2], [2, 0, 1]], dtype=np.uint8)[None, None]
+    assert orc.executed_flops(M, p) == 4 * 4 * 197
+    # all level 1 = dense: 4 N^2 d
+    assert orc.executed_flops(np.ones_like(M), p) == 4 * 19 * 19 * 4
+
+
+def test_executed_flops_is_rho_times_dense_on_whole_blocks():
+    """With b_q | N and b_k | N every block is whole, so token-exact FLOPs = Eq. 9's rho-bar x dense."""
+    p = Params(2, 3, 3, 256, 16, 32, 32, 4)
+    M = np.random.default_rng(8).integers(0, 5, size=(2, 3, p.nq, p.nk)).astype(np.uint8)
+    rho = orc.compute_ratio(M, p).sum()
+    assert orc.executed_flops(M, p) == pytest.approx(rho * 4 * 256 * 256 * 16, rel=1e-12)
