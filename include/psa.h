@@ -17,7 +17,9 @@
  *   - Blocks (Sec. 3.1): nq = ceil(N / bq) query blocks, nk = ceil(N / bk) key blocks; the last block
  *     of either kind may be short (the paper assumes divisibility; see psa_build_pyramid).
  *   - Levels follow Eq. 5:  M = 0 skip,  M = h in 1..H use level h (pooled by 2^(h-1)).
- *   - Return value: PSA_OK, or an error code; on error nothing has been enqueued.
+ *   - Return value: PSA_OK, or an error code.  PSA_EINVAL and PSA_EUNSUPPORTED are decided before any
+ *     work is enqueued.  PSA_ELAUNCH means the HIP runtime refused a launch; kernels of the same call
+ *     enqueued before the refused one still run, and the outputs of the call are then undefined.
  *     No call prints, throws or aborts.
  */
 #ifndef PSA_H
@@ -65,7 +67,7 @@ typedef struct psa_params {
  *                  itself and is not copied).  0 when H = 1.
  *   scratch_bytes  bytes of workspace that psa_allocate_levels and psa_attention_fwd may use
  *                  (representative tokens, scores, per-row block lists).  Contents need not survive
- *                  between calls.  Must be 256-byte aligned.
+ *                  between calls.  Must be 256-byte aligned (PSA_EINVAL otherwise).
  * Either output pointer may be NULL.  Errors: PSA_EINVAL / PSA_EUNSUPPORTED for bad parameters.
  */
 int psa_query_sizes(const psa_params* p, size_t* pyr_bytes, size_t* scratch_bytes);
@@ -102,8 +104,8 @@ int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* K
  *   M           out, uint8 [B, Hq, nq, nk]
  *   rho_out     nullable, float [B, Hq]: achieved compute ratio, Eq. 9, over the visible block pairs
  *   scratch     workspace of psa_query_sizes' scratch_bytes
- * Errors: PSA_EINVAL (null required pointer, tau not monotone / outside [0,1], budget outside (0,1]),
- *         PSA_EUNSUPPORTED (nk > PSA_MAX_NK, d not in {64,128}), PSA_ELAUNCH.
+ * Errors: PSA_EINVAL (null required pointer, misaligned scratch, tau not monotone / outside [0,1], budget
+ *         outside (0,1]), PSA_EUNSUPPORTED (nk > PSA_MAX_NK, d not in {64,128}), PSA_ELAUNCH.
  */
 int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const void* Kpyr,
                         const float* scores_in, float* scores_out, const uint8_t* level_cap,
@@ -116,7 +118,7 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
  * A pooled key covering c valid tokens of a ragged last block is biased by ln c; padding is masked.
  * Causal: a (pooled) key is visible to a query row iff every token it covers is <= the row.
  *   K, V        level 1;  Kpyr, Vpyr  levels 2..H (may be NULL if H = 1)
- *   M           uint8 [B, Hq, nq, nk] (values > H are an error the kernel does not detect: undefined)
+ *   M           uint8 [B, Hq, nq, nk]; a value above H is treated as 0 (the block is skipped)
  *   O           out [B, Hq, N, d], dtype
  *   lse         nullable out, float [B, Hq, N]: natural-log softmax denominator incl. the row max
  *   scratch     workspace of psa_query_sizes' scratch_bytes (per-row level-sorted block lists and per-tile
@@ -124,6 +126,8 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
  * bfloat16: QK^T and PV run on MFMA with fp32 accumulation, P is rounded to bfloat16 before PV.
  * float32: all arithmetic in fp32 with an accurate exp.
  * A row whose kept blocks contain no visible key produces NaN.
+ * Errors: PSA_EINVAL (null required pointer, misaligned scratch), PSA_EUNSUPPORTED (bfloat16 with more
+ *         key blocks per row than fit the kernel's LDS: about 48 000 at d = 128), PSA_ELAUNCH.
  */
 int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const void* V,
                       const void* Kpyr, const void* Vpyr, const uint8_t* M, void* O, float* lse,
@@ -136,23 +140,6 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
  */
 int psa_dense_ref(const psa_params* p, const void* Q, const void* K, const void* V, void* O,
                   float* lse, void* stream);
-
-/*
- * Measurement aids (not part of the method; the benchmark uses them to state what this GPU sustains,
- * next to the published peaks its roofline fractions are quoted against).
- *
- * psa_probe_copy: plain streaming copy of `bytes` (a multiple of 16) from src to dst, both device
- *   pointers of at least that size; moves 2 * bytes through HBM.
- * psa_probe_mfma: `workgroups` workgroups of 4 wavefronts, each wavefront issuing iters * 16
- *   bfloat16 32x32x16 MFMAs on register operands.  random_operands = 0: a few small values (the
- *   least power the matrix pipe can draw); != 0: random signs and mantissas, magnitudes in [0.5, 2),
- *   as real activations have (the sustained rate is markedly lower: the clock follows the power).
- *   sink: device, workgroups * 256 floats (written once).  flops (host pointer, nullable) receives
- *   the floating-point operations of the launch.
- * Both are asynchronous on `stream`; PSA_EINVAL for null pointers or sizes out of range.
- */
-int psa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
-int psa_probe_mfma(float* sink, int workgroups, int iters, int random_operands, double* flops, void* stream);
 
 /* Static description of a status code (host pointer, never NULL). */
 const char* psa_status_str(int status);

@@ -440,8 +440,8 @@ hipError_t launch_tiles(const Plan& pl, const uint16_t* idx, const int32_t* cnt,
   a.pitch = pl.desc_pitch;
   const int64_t rows = (int64_t)pl.B * pl.Hq * pl.nq;
   const size_t smem = ((size_t)pl.nk * sizeof(uint16_t) + 15) & ~(size_t)15;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tiles_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static LdsOptIn optin;
+  const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(tiles_kernel), &optin);
   if (e != hipSuccess) return e;
   tiles_kernel<<<(unsigned)rows, 256, smem, s>>>(idx, cnt, desc, a);
   return hipGetLastError();

@@ -13,7 +13,18 @@ bool importance_uses_mfma(const Plan& pl);
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
-static const size_t LDS_LIMIT = 160 * 1024;
+hipError_t allow_max_lds(const void* kernel, LdsOptIn* state) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (__atomic_load_n(&state->done[dev], __ATOMIC_ACQUIRE)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_LIMIT);
+  if (e == hipSuccess) __atomic_store_n(&state->done[dev], 1, __ATOMIC_RELEASE);
+  return e;
+}
+
+size_t attn_mfma_smem_bytes(int d, int nk, int bn);
 
 int make_plan(const psa_params* p, Plan* o) {
   if (!p || !o) return PSA_EINVAL;
@@ -157,6 +168,7 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
   rc = plan_allocation(p, &pl);
   if (rc != PSA_OK) return rc;
   if (!M || !scratch) return PSA_EINVAL;
+  if (reinterpret_cast<uintptr_t>(scratch) & 255) return PSA_EINVAL;
   if (pl.nk > PSA_MAX_NK) return PSA_EUNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const float* scores = scores_in;
@@ -194,6 +206,9 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
   if (rc != PSA_OK) return rc;
   if (!Q || !K || !V || !M || !O || !scratch) return PSA_EINVAL;
   if (pl.H > 1 && (!Kpyr || !Vpyr)) return PSA_EINVAL;
+  if (reinterpret_cast<uintptr_t>(scratch) & 255) return PSA_EINVAL;
+  // the matrix-core kernel keeps a row's block list in LDS next to its four tiles
+  if (pl.use_mfma && attn_mfma_smem_bytes(pl.d, pl.nk, 64) > LDS_LIMIT) return PSA_EUNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint16_t* idx = reinterpret_cast<uint16_t*>(at(scratch, pl.off_idx));
   int32_t* cnt = reinterpret_cast<int32_t*>(at(scratch, pl.off_cnt));

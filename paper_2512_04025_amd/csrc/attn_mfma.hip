@@ -780,8 +780,8 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) a.lvl_off[h] = pl.lvl_off[h];
   const size_t smem = attn_mfma_smem_bytes(D, pl.nk, BN);
   auto kern = attn_mfma_kernel<D, NW, SC, BN>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)smem);
+  static LdsOptIn optin;                       // one per kernel instantiation
+  const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
   kern<<<((a.items + 7) / 8) * 8, NW * 64, smem, s>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),

@@ -210,8 +210,8 @@ static hipError_t launch_imp_t(const Plan& pl, const void* Qrep, const void* Kre
   a.scale = pl.scale;
   const size_t smem = importance_smem_bytes(pl.sq, pl.nk, D);
   auto kern = importance_kernel<T, D>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  static LdsOptIn optin;                       // one per kernel instantiation
+  const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
   dim3 grid(pl.nq, pl.Hq, pl.B);
   kern<<<grid, 256, smem, s>>>(static_cast<const T*>(Qrep), static_cast<const T*>(Krep), S, a);
@@ -341,7 +341,11 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
   for (int ks = 0; ks < KS; ++ks)
     kaddr[ks] = (uint32_t)(l32 * ROWB + ((hf ^ ((l32 / RP256) % CPR)) << 4)) ^ (uint32_t)(ks << 5);
 
-  const bool rows_full = rg * 128 + 128 <= nrows;
+  // every row of the workgroup exists AND covers at least one token (positions grow with the row, so
+  // the last row decides): a pooled representative past the end of a short last query block is dead
+  // and must take the masked path, where its logits are -inf
+  const bool rows_full = rg * 128 + 128 <= nrows &&
+                         rep_pos(a.mode, (rg * 128 + 127) / SQ, (rg * 128 + 127) % SQ, a.bq, SQ, a.N) >= 0;
   const int gk = a.bk / SK;
   auto is_plain = [&](int tile) __attribute__((always_inline)) {   // all 64 keys and all rows valid, nothing hidden
     const bool keys_full = a.mode == PSA_REP_STRIDED ? tile * BN + BN <= nkeys : (int64_t)(tile * BN + BN - 1) * gk < a.N;
@@ -687,9 +691,10 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
   dim3 grid(row_groups, ksplit, pl.Hq * pl.B);
   auto k1 = importance_tiles_kernel<D, 1>;
   auto k2 = importance_tiles_kernel<D, 2>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, smem1);
+  static LdsOptIn optin1, optin2;              // one per kernel instantiation
+  hipError_t e = allow_max_lds(reinterpret_cast<const void*>(k1), &optin1);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  e = allow_max_lds(reinterpret_cast<const void*>(k2), &optin2);
   if (e != hipSuccess) return e;
   const bool keep_max = pl.est_pool == PSA_EST_MAX;
   a.bm_rows = row_groups * 128;

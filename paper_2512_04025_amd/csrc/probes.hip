@@ -4,6 +4,7 @@
 // behind the published matrix peak).  Not part of the method.
 #include "psa_dev.h"
 #include "psa_internal.h"
+#include "../../include/psa_probe.h"
 
 namespace psa {
 

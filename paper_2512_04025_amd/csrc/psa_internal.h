@@ -28,6 +28,15 @@ struct Plan {
 
 int make_plan(const psa_params* p, Plan* out);
 
+// LDS a workgroup may use on gfx950, and the one-time opt-in that lets a kernel ask for more than the
+// default 64 KB of dynamic LDS.  The limit is raised to the hardware maximum once per kernel and
+// device (never lowered again), so concurrent calls with different problem sizes cannot shrink each
+// other's limit between the opt-in and the launch.  `state` is a zero-initialised per-kernel array.
+constexpr size_t LDS_LIMIT = 160 * 1024;
+constexpr int MAX_DEVICES = 64;
+struct LdsOptIn { int done[MAX_DEVICES]; };
+hipError_t allow_max_lds(const void* kernel, LdsOptIn* state);
+
 // rows of the per-row counters written by the allocation kernel: [n_visible, c_1 .. c_H]
 constexpr int ROWCNT_STRIDE = PSA_MAX_LEVELS + 1;
 // per-row level counts consumed by the attention kernels: c_1 .. c_H

@@ -115,18 +115,25 @@ def _positions(w: Workload, n_field: int) -> np.ndarray:
     return np.stack([t / T, y / Hg, x / W], axis=1)  # [n, 3]; t may exceed T-1 only if N > grid size
 
 
-def _field(rng: np.random.Generator, phase_n: np.ndarray, d: int, n_text: int, gain: float) -> np.ndarray:
-    """One [N, d] tensor.  phase_n: [n_field, 8] = 2 pi f_m . p_n."""
+def _draw(rng: np.random.Generator, n_field: int, d: int, n_text: int):
+    """Every random number one [N, d] tensor needs, in the fixed draw order (amplitudes, phases, noise,
+    text rows).  Only this part touches the generator, so it stays on the calling thread."""
     A = rng.standard_normal((8, d)) / np.sqrt(8.0)
     phi = rng.uniform(0.0, 2.0 * np.pi, size=(8, d))
+    noise = rng.standard_normal((n_field, d))
+    text = rng.standard_normal((n_text, d)) if n_text else None
+    return A, phi, noise, text
+
+
+def _finish(draw, cos_n: np.ndarray, sin_n: np.ndarray, gain: float, dtype: str, out: np.ndarray) -> None:
+    """The arithmetic of one tensor from its draws (no randomness: may run on a worker thread)."""
+    A, phi, noise, text = draw
     # cos(theta_n + phi_d) = cos(theta_n) cos(phi_d) - sin(theta_n) sin(phi_d): two rank-8 products
-    smooth = np.cos(phase_n) @ (A * np.cos(phi)) - np.sin(phase_n) @ (A * np.sin(phi))
-    noise = rng.standard_normal(smooth.shape)
+    smooth = cos_n @ (A * np.cos(phi)) - sin_n @ (A * np.sin(phi))
     x = gain * (smooth + 0.5 * noise)
-    if n_text:
-        text = rng.standard_normal((n_text, d))
+    if text is not None:
         x = np.concatenate([text, x], axis=0)
-    return x.astype(np.float32)
+    out[...] = _store(x.astype(np.float32), dtype)
 
 
 def _store(x32: np.ndarray, dtype: str) -> np.ndarray:
@@ -136,7 +143,11 @@ def _store(x32: np.ndarray, dtype: str) -> np.ndarray:
 def generate_qkv(w: Workload):
     """Return (Q, K, V): Q [B,Hq,N,d], K,V [B,Hkv,N,d]; float32 arrays for dtype 'f32', uint16
     bfloat16 bit patterns for 'bf16'.  Query head hq shares the frequency bank of its key/value
-    head hq // (Hq // Hkv); everything else about it is drawn independently."""
+    head hq // (Hq // Hkv); everything else about it is drawn independently.  The random numbers are
+    drawn on the calling thread in a fixed order; the arithmetic on them runs on a few worker threads
+    (same operations on the same numbers: the bytes do not depend on the thread count)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
     rng = np.random.default_rng(w.seed)
     n_field = w.N - w.text_tokens
     pos = _positions(w, n_field)
@@ -145,17 +156,29 @@ def generate_qkv(w: Workload):
     K = np.empty((w.B, w.Hkv, w.N, w.d), dtype=store_dt)
     V = np.empty((w.B, w.Hkv, w.N, w.d), dtype=store_dt)
     group = w.Hq // w.Hkv
-    for b in range(w.B):
-        for hk in range(w.Hkv):
-            lo = int(rng.integers(0, 5)) if w.per_head_band else 0
-            bank = rng.integers(lo, lo + 4, size=(8, 3)).astype(np.float64)
-            phase_n = 2.0 * np.pi * (pos @ bank.T)          # [n_field, 8]
-            for g in range(group):
-                gain = float(rng.normal(1.0, 0.1)) if w.per_head_gain else 1.0
-                Q[b, hk * group + g] = _store(_field(rng, phase_n, w.d, w.text_tokens, gain), w.dtype)
+    workers = max(1, min(8, (os.cpu_count() or 2) - 1))
+    pending = []
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        def submit(out, cos_n, sin_n):
             gain = float(rng.normal(1.0, 0.1)) if w.per_head_gain else 1.0
-            K[b, hk] = _store(_field(rng, phase_n, w.d, w.text_tokens, gain), w.dtype)
-            V[b, hk] = _store(_field(rng, phase_n, w.d, w.text_tokens, gain), w.dtype)
+            draw = _draw(rng, n_field, w.d, w.text_tokens)
+            pending.append(pool.submit(_finish, draw, cos_n, sin_n, gain, w.dtype, out))
+            while len(pending) > 2 * workers:          # bounds the draws held in memory
+                pending.pop(0).result()
+        for b in range(w.B):
+            for hk in range(w.Hkv):
+                lo = int(rng.integers(0, 5)) if w.per_head_band else 0
+                bank = rng.integers(lo, lo + 4, size=(8, 3)).astype(np.float64)
+                phase_n = 2.0 * np.pi * (pos @ bank.T)          # [n_field, 8]
+                cos_n, sin_n = np.cos(phase_n), np.sin(phase_n)
+                for g in range(group):
+                    submit(Q[b, hk * group + g], cos_n, sin_n)
+                gain = float(rng.normal(1.0, 0.1)) if w.per_head_gain else 1.0
+                for out in (K[b, hk], V[b, hk]):           # K and V share the head's gain
+                    draw = _draw(rng, n_field, w.d, w.text_tokens)
+                    pending.append(pool.submit(_finish, draw, cos_n, sin_n, gain, w.dtype, out))
+        for f in pending:
+            f.result()
     return Q, K, V
 
 

@@ -20,8 +20,9 @@ def lib():
 
 
 def test_header_symbols_are_exported(lib):
-    header = open(os.path.join(ROOT, "include", "psa.h")).read()
-    names = set(re.findall(r"\b(psa_[a-z_]+)\s*\(", header))
+    import glob
+    header = "".join(open(f).read() for f in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
+    names = set(re.findall(r"\b(psa_[a-z_0-9]+)\s*\(", header))
     assert {"psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_dense_ref",
             "psa_status_str"} <= names
     for n in names:
@@ -70,6 +71,20 @@ def test_null_pointers_and_bad_rules_fail_before_any_launch(lib):
     pb.budget = 1.5
     assert lib.psa_allocate_levels(ctypes.byref(pb), None, None, None, one, None, None, one, None, one, None) == 1
     assert psa.psa_status_str(0) == "ok" and "unknown" in psa.psa_status_str(99)
+
+
+def test_misaligned_scratch_is_rejected(lib):
+    p = psa.make_params(1, 2, 2, 1024, 64, 64, 64, 4)
+    pp = ctypes.byref(p)
+    one, odd = ctypes.c_void_p(256), ctypes.c_void_p(256 + 16)   # never dereferenced: validation fails first
+    assert lib.psa_allocate_levels(pp, None, None, None, one, None, None, one, None, odd, None) == 1
+    assert lib.psa_attention_fwd(pp, one, one, one, one, one, one, one, None, odd, None) == 1
+
+
+def test_rows_too_long_for_the_attention_kernels_lds_are_unsupported(lib):
+    p = psa.make_params(1, 1, 1, 64 * 50000, 128, 128, 64, 1)
+    one = ctypes.c_void_p(256)
+    assert lib.psa_attention_fwd(ctypes.byref(p), one, one, one, None, None, one, one, None, one, None) == 2
 
 
 def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
