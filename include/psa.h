@@ -134,6 +134,21 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
                       void* scratch, void* stream);
 
 /*
+ * psa_attention_fwd for callers that cannot hand over a workspace or allocate one: code recorded into
+ * a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus `scratch`),
+ * same kernels and bit-identical results; the per-row block lists and tile descriptors live in a
+ * static device array of PSA_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until
+ * the process ends.  The call allocates and frees nothing.  A problem whose lists and descriptors need
+ * more than that returns PSA_EUNSUPPORTED (use psa_attention_fwd).  All calls on one GPU share the
+ * array: calls that overlap in time on one GPU (two streams, two threads) race and must be serialised
+ * by the caller.  The array's address is looked up on the first call on each device.
+ */
+#define PSA_STATIC_SCRATCH_BYTES (32u << 20)
+int psa_attention_fwd_static(const psa_params* p, const void* Q, const void* K, const void* V,
+                             const void* Kpyr, const void* Vpyr, const uint8_t* M, void* O, float* lse,
+                             void* stream);
+
+/*
  * Dense softmax attention, Eq. 1 (optionally causal / grouped-query): O = Softmax(Q K^T * scale) V.
  * A simple fp32-accumulate kernel meant as a reference, not as a fast path.
  *   O  out [B, Hq, N, d], dtype;  lse nullable out, float [B, Hq, N].

@@ -63,12 +63,13 @@ def load_library() -> ctypes.CDLL:
     lib.psa_build_pyramid.argtypes = [pp, vp, vp, vp, vp, vp]
     lib.psa_allocate_levels.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.psa_attention_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_dense_ref.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.psa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.psa_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
-    for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd",
+    for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_attention_fwd_static",
                  "psa_dense_ref", "psa_probe_copy", "psa_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -138,6 +139,12 @@ def psa_attention_fwd(p: PsaParams, Q, K, V, Kpyr, Vpyr, M, O, scratch, lse=None
     _check(load_library().psa_attention_fwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(Kpyr), _ptr(Vpyr),
                                             _ptr(M), _ptr(O), _ptr(lse), _ptr(scratch), _stream(stream)),
            "psa_attention_fwd")
+
+
+def psa_attention_fwd_static(p: PsaParams, Q, K, V, Kpyr, Vpyr, M, O, lse=None, stream=None) -> None:
+    _check(load_library().psa_attention_fwd_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(Kpyr),
+                                                   _ptr(Vpyr), _ptr(M), _ptr(O), _ptr(lse), _stream(stream)),
+           "psa_attention_fwd_static")
 
 
 def psa_dense_ref(p: PsaParams, Q, K, V, O, lse=None, stream=None) -> None:

@@ -231,6 +231,55 @@ int psa_dense_ref(const psa_params* p, const void* Q, const void* K, const void*
   return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 
+// ---- psa_attention_fwd_static: the same kernels, their workspace in a static device array.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the address the kernels get
+// is looked up once per device (each GPU holds its own copy) and kept in static_ptr.
+static __device__ __align__(256) unsigned char scratch[PSA_STATIC_SCRATCH_BYTES];
+static void* static_ptr[MAX_DEVICES];
+
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return PSA_ELAUNCH;
+  void* ptr = __atomic_load_n(&static_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PSA_ELAUNCH;
+    __atomic_store_n(&static_ptr[dev], ptr, __ATOMIC_RELEASE);
+  }
+  *out = ptr;
+  return PSA_OK;
+}
+
+int psa_attention_fwd_static(const psa_params* p, const void* Q, const void* K, const void* V, const void* Kpyr,
+                             const void* Vpyr, const uint8_t* M, void* O, float* lse, void* stream) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  if (!Q || !K || !V || !M || !O) return PSA_EINVAL;
+  if (pl.H > 1 && (!Kpyr || !Vpyr)) return PSA_EINVAL;
+  if (pl.use_mfma && attn_mfma_smem_bytes(pl.d, pl.nk, 64) > LDS_LIMIT) return PSA_EUNSUPPORTED;
+  // only the attention call's part of the workspace: block lists, level counts, tile descriptors
+  const size_t rows_q = (size_t)pl.B * pl.Hq * pl.nq;
+  const size_t off_idx = 0;
+  const size_t off_cnt = off_idx + align256(rows_q * pl.nk * sizeof(uint16_t));
+  const size_t off_desc = off_cnt + align256(rows_q * CNT_STRIDE * sizeof(int32_t));
+  const size_t need = off_desc + align256(rows_q * (size_t)pl.desc_pitch * pl.desc_words * sizeof(uint32_t));
+  if (need > (size_t)PSA_STATIC_SCRATCH_BYTES) return PSA_EUNSUPPORTED;
+  void* base = nullptr;
+  const int rs = static_scratch(&base);
+  if (rs != PSA_OK) return rs;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint16_t* idx = reinterpret_cast<uint16_t*>(at(base, off_idx));
+  int32_t* cnt = reinterpret_cast<int32_t*>(at(base, off_cnt));
+  uint32_t* desc = reinterpret_cast<uint32_t*>(at(base, off_desc));
+  // every word the attention kernel reads is rewritten by the two kernels below, so nothing needs
+  // clearing between calls (what an earlier, larger call left behind is never read)
+  if (launch_schedule(pl, M, idx, cnt, s) != hipSuccess) return PSA_ELAUNCH;
+  if (pl.desc_pitch > 0 && launch_tiles(pl, idx, cnt, desc, s) != hipSuccess) return PSA_ELAUNCH;
+  const hipError_t e = pl.use_mfma ? launch_attn_mfma(pl, Q, K, V, Kpyr, Vpyr, idx, cnt, desc, O, lse, s)
+                                   : launch_attn_rows(pl, Q, K, V, Kpyr, Vpyr, idx, cnt, O, lse, s);
+  return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
 const char* psa_status_str(int status) {
   switch (status) {
     case PSA_OK: return "ok";
