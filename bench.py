@@ -3,8 +3,10 @@
 One step = psa_build_pyramid + psa_allocate_levels + psa_attention_fwd over one synthetic batch that
 is already resident in HBM.  Prints ONE JSON line: whole-path dense-equivalent TFLOP/s (dense FLOPs of
 the same attention problem divided by the PSA step time), ms per step, the roofline of the dominant
-kernel (the MFMA attention kernel, on EXECUTED FLOPs), the HBM roofline of the pyramid pass, and the
-CPU oracle timed on a bounded sample of the same workload.
+kernel (the MFMA attention kernel, on EXECUTED FLOPs), the HBM rooflines of the pyramid pass and of
+the whole pre-pass (pyramid + importance + allocation), the error against dense attention, a parity
+check of the timed configuration against the CPU oracle (outside the timed region), a second point
+with the threshold rule of Alg. 2, and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -38,7 +40,10 @@ def parse_args():
                     help="also run one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-only microbenchmarks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--check-dense", action="store_true", help="also report rel-L2 of PSA vs dense attention")
+    ap.add_argument("--no-check-dense", action="store_true", help="skip rel-L2 of PSA vs dense attention")
+    ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of sampled query blocks")
+    ap.add_argument("--no-threshold-point", action="store_true",
+                    help="skip the second point with Alg. 2's threshold rule (tau = 0.5, 0.7, 0.8, 0.9)")
     return ap.parse_args()
 
 
@@ -69,17 +74,32 @@ def pyramid_bytes(w, levels: int) -> float:
     return 2.0 * w.B * w.Hkv * w.N * w.d * e * frac
 
 
+def prepass_bytes(w, levels: int, nq: int, nk: int) -> float:
+    """Algorithmic HBM bytes of pyramid + importance + allocation: K and V read once and the pooled
+    levels written once; Q read once (its 8 pooled representatives per block are formed on the fly);
+    the level-H keys read once per head as representative keys; S written and read once (fp32) and M
+    written once (uint8)."""
+    e = 2 if w.dtype == "bf16" else 4
+    q_bytes = float(w.B) * w.Hq * w.N * w.d * e
+    krep_bytes = float(w.B) * w.Hkv * nk * (w.bk >> (levels - 1)) * w.d * e if levels > 1 else 0.0
+    sm_bytes = float(w.B) * w.Hq * nq * nk * (4 + 4 + 1)
+    return pyramid_bytes(w, levels) + q_bytes + krep_bytes + sm_bytes
+
+
 def measured_traffic(w, budget, kernel_prefix: str):
-    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary for this exact
-    workload and budget (FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel calibration); None otherwise."""
-    path = os.path.join(ROOT, "profiles", f"psa_fwd_{w.name}_budget{budget}_traffic.json")
+    """(bytes, source): HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary
+    for this exact workload and budget (FETCH_SIZE / WRITE_SIZE scaled by the copy-kernel calibration).
+    The counters cannot be read from inside this process, so the figure is the one of the committed
+    profile, named in `source`; (None, None) when there is no profile for the workload."""
+    rel = os.path.join("profiles", f"psa_fwd_{w.name}_budget{budget}_traffic.json")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     rec = json.load(open(path))
     for name, v in rec["kernels"].items():
         if name.startswith(kernel_prefix):
-            return v["read_bytes"] + v["write_bytes"]
-    return None
+            return v["read_bytes"] + v["write_bytes"], rel
+    return None, None
 
 
 def attainable_peaks(torch, psa):
@@ -159,6 +179,50 @@ def cpu_baseline(w, budget, Q, K, V, n_heads: int = 3):
     }
 
 
+def parity_leg(w, gp, budget, Q, K, V, buf, torch):
+    """A few query blocks of the LAST (batch, head) of the timed configuration against the oracle, under
+    the level map the timed run itself produced: a timed run can never be a wrong run unnoticed."""
+    import synth_inputs as si
+    from oracle import psa_oracle as orc
+    from paper_2512_04025_amd.plumbing import from_dev
+    from tests.psa_testlib import oracle_params
+    b, hq = w.B - 1, w.Hq - 1
+    hk = hq // (w.Hq // w.Hkv)
+    op1 = oracle_params(w, budget=budget, B=1, Hq=1, Hkv=1)
+    Q1 = si.to_f64(Q[b:b + 1, hq:hq + 1], w.dtype)
+    K1 = si.to_f64(K[b:b + 1, hk:hk + 1], w.dtype)
+    V1 = si.to_f64(V[b:b + 1, hk:hk + 1], w.dtype)
+    M1 = buf.M[b:b + 1, hq:hq + 1].cpu().numpy()
+    qblocks = sorted({0, op1.nq // 2, op1.nq - 1})
+    O1, _ = orc.psa_attention(Q1, orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1), M1, op1, q_blocks=qblocks)
+    max_abs, num, den = 0.0, 0.0, 0.0
+    for i in qblocks:
+        rows = slice(i * w.bq, min((i + 1) * w.bq, w.N))
+        got, ref = from_dev(buf.O[b, hq, rows], w.dtype), O1[0, 0][rows]
+        max_abs = max(max_abs, float(np.abs(got - ref).max()))
+        num += float(((got - ref) ** 2).sum())
+        den += float((ref ** 2).sum())
+    return {"parity_max_abs": max_abs, "parity_rel_l2": float(np.sqrt(num / den)),
+            "parity_sample": f"batch {b} head {hq}, query blocks {qblocks} vs the CPU oracle under the run's own level map"}
+
+
+def timed_phases(torch, fns, steps):
+    """HIP events around each call of `fns` on the current stream, `steps` times; returns
+    (wall ms per step, [mean ms per call], [median ms per call])."""
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        ev[k][0].record()
+        for c, fn in enumerate(fns):
+            fn()
+            ev[k][c + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = np.array([[e[c].elapsed_time(e[c + 1]) for c in range(len(fns))] for e in ev])
+    return (t1 - t0) * 1e3 / steps, per.mean(axis=0).tolist(), np.median(per, axis=0).tolist()
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -180,22 +244,28 @@ def main():
         hq = args.heads or w.Hq
         w = si.small_variant(w, args.seq or w.N, Hq=hq, Hkv=max(1, hq * w.Hkv // w.Hq))
     budget = args.budget if args.budget is not None else w.budget
-    gp = psa.make_params(w.B, w.Hq, w.Hkv, w.N, w.d, w.bq, w.bk, w.levels,
-                         dtype=psa.PSA_BF16 if w.dtype == "bf16" else psa.PSA_F32, causal=w.causal,
-                         sq=sq, sk=sk, rep_mode=psa.PSA_REP_POOLED, est_pool=psa.PSA_EST_MAX,
-                         alloc_mode=psa.PSA_ALLOC_BUDGET, budget=budget)
+
+    def params(**kw):
+        base = dict(dtype=psa.PSA_BF16 if w.dtype == "bf16" else psa.PSA_F32, causal=w.causal, sq=sq, sk=sk,
+                    rep_mode=psa.PSA_REP_POOLED, est_pool=psa.PSA_EST_MAX, alloc_mode=psa.PSA_ALLOC_BUDGET, budget=budget)
+        base.update(kw)
+        return psa.make_params(w.B, w.Hq, w.Hkv, w.N, w.d, w.bq, w.bk, w.levels, **base)
+
+    gp = params()
     torch.cuda.set_device(0)
     Q, K, V = si.generate_qkv(w)
     Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
     buf = Buffers(gp)
 
-    def step():
-        psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
-        psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho)
-        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)
+    # the two microbenchmarks run first: they also bring the clock to its sustained state
+    att = None if args.no_attainable else attainable_peaks(torch, psa)
 
+    calls = [lambda: psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr),
+             lambda: psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho),
+             lambda: psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)]
     for _ in range(args.warmup):
-        step()
+        for fn in calls:
+            fn()
     torch.cuda.synchronize()
     if args.copy_probe_mb:
         src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device="cuda")
@@ -203,22 +273,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        ev[k][0].record()
-        psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
-        ev[k][1].record()
-        psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho)
-        ev[k][2].record()
-        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)
-        ev[k][3].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_step = (t1 - t0) * 1e3 / args.steps
-    ms_pyr = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    ms_alloc = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    ms_attn = float(np.mean([e[2].elapsed_time(e[3]) for e in ev]))
+    ms_step, mean_ms, median_ms = timed_phases(torch, calls, args.steps)
+    ms_pyr, ms_alloc, ms_attn = mean_ms
 
     M = buf.M.cpu().numpy()
     rho = float(buf.rho.mean().item())
@@ -227,6 +283,10 @@ def main():
     fl_dense = dense_flops(w)
     attn_tflops = fl_exec / (ms_attn * 1e-3) / 1e12
     pyr_gbs = pyramid_bytes(w, w.levels) / (ms_pyr * 1e-3) / 1e9 if w.levels > 1 else None
+    pre_bytes = prepass_bytes(w, w.levels, gp.nq, gp.nk)
+    pre_gbs = pre_bytes / ((ms_pyr + ms_alloc) * 1e-3) / 1e9
+    attn_traffic, attn_src = measured_traffic(w, budget, "psa::attn_mfma_kernel")
+    pyr_traffic, pyr_src = measured_traffic(w, budget, "psa::pyramid_kernel")
 
     out = {
         "metric": "psa_fwd_dense_equivalent_tflops", "value": fl_dense / (ms_step * 1e-3) / 1e12,
@@ -237,32 +297,70 @@ def main():
                                f"levels={w.levels} causal={int(w.causal)} budget={budget}",
                    "alloc_mode": "budget", "rep_mode": "pooled", "est_pool": "max"},
         "phases_ms": {"build_pyramid": ms_pyr, "allocate_levels": ms_alloc, "attention_fwd": ms_attn},
+        "phases_ms_median": dict(zip(("build_pyramid", "allocate_levels", "attention_fwd"), median_ms)),
         "achieved_rho": rho, "kv_coverage": coverage,
         "executed_tflop": fl_exec / 1e12, "dense_tflop": fl_dense / 1e12,
         "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic(w, budget, "psa::attn_mfma_kernel"),
-                     "note": "executed FLOPs / mean HIP-event time of psa_attention_fwd (includes its block-list and tile-descriptor kernels)"},
+                     "traffic": attn_traffic, "traffic_source": attn_src,
+                     "note": "executed FLOPs / mean HIP-event time of psa_attention_fwd (includes its block-list and tile-descriptor kernel)"},
         "roofline_pyramid": None if pyr_gbs is None else {
             "kernel": "pyramid_kernel", "bound": "hbm", "achieved": pyr_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": measured_traffic(w, budget, "psa::pyramid_kernel"),
+            "frac": pyr_gbs / PEAK_HBM_GBS, "traffic": pyr_traffic, "traffic_source": pyr_src,
             "algorithmic_bytes": pyramid_bytes(w, w.levels)},
+        "roofline_prepass": {
+            "kernels": "psa_build_pyramid + psa_allocate_levels (pyramid, representatives, importance, allocation)",
+            "bound": "hbm", "achieved": pre_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": pre_gbs / PEAK_HBM_GBS,
+            "algorithmic_bytes": pre_bytes,
+            "note": "K, V read + pooled levels written + Q read + level-H keys read + S written and read + M written, "
+                    "over the mean HIP-event time of the two calls"},
     }
-    if not args.no_attainable:
-        att = attainable_peaks(torch, psa)
+    if att is not None:
         out["attainable"] = att
         out["roofline"]["frac_of_attainable"] = attn_tflops / att["mfma_bf16_tflops"]
         out["roofline"]["frac_of_attainable_random_operands"] = attn_tflops / att["mfma_bf16_tflops_random_operands"]
         if pyr_gbs is not None:
             out["roofline_pyramid"]["frac_of_attainable"] = pyr_gbs / att["hbm_copy_gbs"]
+        out["roofline_prepass"]["frac_of_attainable"] = pre_gbs / att["hbm_copy_gbs"]
     if w.dtype != "bf16":
         out["roofline"]["note"] += "; fp32 mode runs on the VALU (correctness mode), bf16 MFMA peak shown for scale only"
-    if args.check_dense:
+    if not args.no_parity:
+        out.update(parity_leg(w, gp, budget, Q, K, V, buf, torch))
+    if not args.no_check_dense:
+        # dense attention = the same call with every block at level 1 (that equality is a parity test)
         dense = torch.empty_like(buf.O)
-        psa.psa_dense_ref(gp, Qd, Kd, Vd, dense)
+        ones = torch.ones_like(buf.M)
+        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, ones, dense, buf.scratch)
         torch.cuda.synchronize()
-        a, b = from_dev(buf.O, w.dtype), from_dev(dense, w.dtype)
-        out["rel_l2_vs_dense"] = float(np.linalg.norm(a - b) / np.linalg.norm(b))
+        num = den = 0.0
+        for b in range(w.B):            # head by head: the fp64 copies stay small
+            for h in range(w.Hq):
+                x, y = from_dev(buf.O[b, h], w.dtype), from_dev(dense[b, h], w.dtype)
+                num += float(((x - y) ** 2).sum())
+                den += float((y ** 2).sum())
+        out["rel_l2_vs_dense"] = float(np.sqrt(num / den))
+        del dense, ones
+    if not args.no_threshold_point and w.levels == 4:
+        # Alg. 2 with the thresholds the paper prints for its ablation; the compute ratio is whatever results
+        tau = (0.5, 0.7, 0.8, 0.9)
+        gt = params(alloc_mode=psa.PSA_ALLOC_THRESHOLD, tau=tau)
+        tcalls = [lambda: psa.psa_allocate_levels(gt, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho),
+                  lambda: psa.psa_attention_fwd(gt, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)]
+        for _ in range(5):
+            for fn in tcalls:
+                fn()
+        _, tmean, _ = timed_phases(torch, tcalls, 20)
+        Mt = buf.M.cpu().numpy()
+        fl_t = executed_flops(Mt, w, w.levels)
+        rows_len = (Mt > 0).sum(axis=-1)
+        out["threshold_point"] = {
+            "rule": "Alg. 2", "tau": list(tau), "achieved_rho": float(buf.rho.mean().item()),
+            "kv_coverage": float((Mt > 0).mean()) if not w.causal else None,
+            "kept_blocks_per_row_min_max": [int(rows_len.min()), int(rows_len.max())],
+            "allocate_levels_ms": tmean[0], "attention_fwd_ms": tmean[1], "executed_tflop": fl_t / 1e12,
+            "attention_frac_of_peak": fl_t / (tmean[1] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "dense_equivalent_tflops": fl_dense / ((ms_pyr + tmean[0] + tmean[1]) * 1e-3) / 1e12,
+        }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, budget, Q, K, V)
     print(json.dumps(out))

@@ -110,16 +110,32 @@ void attn_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
-  // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
-  // contiguous run of (head, query block) items, so the workgroups that share an L2 at any moment are
-  // neighbouring query blocks of one head: they keep similar key blocks and walk them in the same order.
-  const int per_xcd = (a.items + 7) >> 3;
-  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per_xcd || item >= a.items) return;
-  const int slice = item % a.slices;
-  int i = (item / a.slices) % a.nq;
+  // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2; the memory-side cache is
+  // shared by all).  Non-causal: all XCDs walk the SAME head at a time, heads outermost, so the
+  // key/value pyramids in flight chip-wide are those of one or two heads, which the memory-side cache
+  // holds whole (with every XCD on a head of its own, eight 73 MB pyramids of the 75600-token shape
+  // are not: measured 6 % slower).  Within a head every XCD takes one contiguous run of query blocks:
+  // neighbours keep similar key blocks and walk them in the same order.  Causal rows differ in length
+  // by up to the whole sequence, so there every XCD takes one contiguous run of (head, query block)
+  // items instead (equal shares of every head's long and short rows), longest rows first.
+  int head, e_item;
+  if (a.causal) {
+    const int per_xcd = (a.items + 7) >> 3;
+    const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || item >= a.items) return;
+    head = item / (a.slices * a.nq);
+    e_item = item - head * (a.slices * a.nq);
+  } else {
+    const int per_head = a.nq * a.slices;
+    const int run = (per_head + 7) >> 3;     // workgroups per XCD and head
+    const int slot = (int)(blockIdx.x >> 3);
+    head = slot / run;
+    e_item = (int)(blockIdx.x & 7) * run + (slot - head * run);
+    if (e_item >= per_head) return;
+  }
+  const int slice = e_item % a.slices;
+  int i = e_item / a.slices;
   if (a.causal) i = a.nq - 1 - i;            // longest rows first
-  const int head = item / (a.slices * a.nq);
   const int b = head / a.Hq, hq = head % a.Hq;
   const int hk = hq / (a.Hq / a.Hkv);
   const int64_t qhead = (int64_t)b * a.Hq + hq;
@@ -783,7 +799,9 @@ static hipError_t launch_mfma_t(const Plan& pl, const void* Q, const void* K, co
   static LdsOptIn optin;                       // one per kernel instantiation
   const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
-  kern<<<((a.items + 7) / 8) * 8, NW * 64, smem, s>>>(
+  const unsigned grid = pl.causal ? (unsigned)((a.items + 7) / 8) * 8u
+                                 : (unsigned)(pl.B * pl.Hq) * 8u * (unsigned)((pl.nq * a.slices + 7) / 8);
+  kern<<<grid, NW * 64, smem, s>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V),
       static_cast<const bf16_t*>(Kp), static_cast<const bf16_t*>(Vp), idx, cnt, desc, static_cast<bf16_t*>(O), lse, a);
   return hipGetLastError();
