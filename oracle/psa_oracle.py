@@ -13,7 +13,8 @@ vs. the recursive 2:1 pooling of Eq. 2-3; PSA with M == 1 vs. dense; PSA on keys
 every pooling group vs. dense restricted to the kept blocks (catches a missing/wrong (h-1) ln 2);
 the one-softmax form of Eq. 8 vs. Alg. 1's online recurrence; importance
 with s_q = b_q, s_k = b_k vs. block-max / block-mean of the brute-force attention matrix; Alg. 2 on
-hand-computed rows; Eq. 9 on the printed preset table (Table 9).  No function here is unpinned
+hand-computed rows; Eq. 9 on the printed preset table (Table 9); the similarity cap of Alg. 3 on the
+two identities App. B.1 states (thresholds -1 / 1), a hand-computed planar example and a loop brute force.  No function here is unpinned
 against the paper's definitions; end-to-end *quality* on real model activations is unpinned (the
 activations are not available) and only its direction is tested on synthetic data.
 """
@@ -342,6 +343,63 @@ def kv_coverage(M: np.ndarray, p: Params) -> np.ndarray:
     """Fraction of visible KV blocks that are kept (level > 0), per (batch, head)  (App. C.4)."""
     vis = block_visibility(p) > 0
     return ((M > 0) & vis[None, None]).sum(axis=(2, 3)) / float(vis.sum())
+
+
+# --------------------------------------------------------------------------- Alg. 3: similarity cap
+COS_EPS = 1e-8   # a pair's cosine is dot / max(|a| |b|, COS_EPS): a zero vector gives 0
+
+
+def block_similarities(K: np.ndarray, p: Params) -> np.ndarray:
+    """sim_h(j) of App. B.1 / Alg. 3 for every (batch, key head, key block): [B, Hkv, nk, H-1], entry
+    h-2 holding level h = 2..H.
+
+    Reading ("stride-2^(h-1) pairs"): the pairs of tokens of the block that lie 2^(h-1) apart,
+    (t, t + 2^(h-1)) with both tokens inside the block and inside the sequence; sim_h is the plain mean
+    of their cosine similarities.  Reading (ragged tail / short blocks, paper assumes whole blocks):
+    a block that holds no such pair gets sim_h = 1 (nothing in it is dissimilar), which keeps the two
+    identities the paper states: all thresholds -1 give L = H everywhere, all thresholds 1 give L = 1.
+    """
+    B, Hkv, N, d = K.shape
+    H = p.levels
+    sims = np.ones((B, Hkv, p.nk, max(H - 1, 0)), dtype=np.float64)
+    norm = np.sqrt((K * K).sum(axis=-1))                                   # [B, Hkv, N]
+    for h in range(2, H + 1):
+        s = 1 << (h - 1)
+        for j in range(p.nk):
+            lo, hi = j * p.bk, min((j + 1) * p.bk, N)
+            if hi - lo <= s:
+                continue
+            a, b = K[:, :, lo:hi - s], K[:, :, lo + s:hi]
+            dot = (a * b).sum(axis=-1)
+            den = np.maximum(norm[:, :, lo:hi - s] * norm[:, :, lo + s:hi], COS_EPS)
+            sims[:, :, j, h - 2] = (dot / den).mean(axis=-1)
+    return sims
+
+
+def similarity_level_cap(K: np.ndarray, p: Params, tau_s: Sequence[float], reduce: str = "per_head"):
+    """Maximum admissible level L of every key block, Alg. 3: L = 1, and for h = 2..H, if
+    sim_h > tau_s^(h) then L = max(L, h) (every level is tested; a failed level does not stop the loop).
+
+    tau_s: H-1 thresholds for levels 2..H (carried as float32).  Returns (L [B, Hkv, nk] uint8, sims).
+    Reading (reduction over batch and heads): Alg. 3 views a key block as a [B, heads, b_k, d] tensor and
+    returns one L per block, i.e. the mean also runs over batch and heads: reduce = "all_heads" (the
+    same L for every batch entry and head).  reduce = "per_head" keeps one L per (batch, key head),
+    the mean running over the block's pairs only; it is what the level_cap input of the allocation takes.
+    """
+    H = p.levels
+    if len(tau_s) < H - 1:
+        raise ValueError("need H-1 similarity thresholds")
+    sims = block_similarities(K, p)
+    use = sims
+    if reduce == "all_heads":
+        use = np.broadcast_to(sims.mean(axis=(0, 1), keepdims=True), sims.shape)
+    elif reduce != "per_head":
+        raise ValueError(reduce)
+    L = np.ones(sims.shape[:3], dtype=np.uint8)
+    for h in range(2, H + 1):
+        ok = use[..., h - 2] > float(np.float32(tau_s[h - 2]))
+        L = np.where(ok, np.maximum(L, h), L).astype(np.uint8)
+    return L, sims
 
 
 # --------------------------------------------------------------------------- Alg. 1: PSA attention

@@ -14,6 +14,8 @@ struct AllocArgs {
   int N, Hq, Hkv, nq, nk, bq, bk, H, causal, mode;
   float tau[PSA_MAX_LEVELS];
   double cuts[PSA_MAX_LEVELS];
+  FactoredScores fs;             // used by the FACTORED instantiation
+  float* S_out;                  // FACTORED: nullable, receives the evaluated scores
 };
 
 // 0 invisible, 1 fully visible, 2 straddles the causal diagonal
@@ -74,15 +76,61 @@ __device__ __forceinline__ uint64_t lane_xor64(uint64_t v, int m) {
 // positions l*KPL .. l*KPL+KPL-1.  Bitonic stages whose partner distance is below KPL exchange
 // registers of one lane (register numbers are compile-time); longer distances exchange the same
 // register between lanes l and l ^ m.  No LDS traffic and no barrier in the sort.
-template <int KPL>
+// FACTORED: the scores are evaluated here from the matrix-core importance sweep's block maxima and
+// softmax statistics (max pooling of Eq. 4: S_ij = 2^(max over the block's 8 rows of (largest logit - lse)))
+// instead of being read from memory.
+template <int KPL, bool FACTORED>
 __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, const uint8_t* __restrict__ cap,
                                                    uint8_t* __restrict__ M, uint32_t* __restrict__ rowcnt,
                                                    AllocArgs a) {
   __shared__ int cnt_s[PSA_MAX_LEVELS + 1];
+  __shared__ float lse_s[8];
   const int lane = threadIdx.x;
   const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
-  const int64_t row = ((int64_t)b * a.Hq + hq) * a.nq + i;
-  const float* s_row = S + row * a.nk;
+  const int64_t head = (int64_t)b * a.Hq + hq;
+  const int64_t row = head * a.nq + i;
+  const float* s_row = FACTORED ? nullptr : S + row * a.nk;
+  const float* bm0 = nullptr;
+  if (FACTORED) {
+    if (lane < 8) {     // lse of the block's 8 representative rows from the key slices' partial results
+      const float2* pr = a.fs.part + ((head * a.nq + i) * 8 + lane) * 8;
+      float mrow = -INFINITY, lrow = 0.f;
+      for (int s2 = 0; s2 < a.fs.ksplit; ++s2) mrow = fmaxf(mrow, pr[s2].x);
+      for (int s2 = 0; s2 < a.fs.ksplit; ++s2) {
+        const float2 v = pr[s2];
+        if (v.x != -INFINITY) lrow += v.y * __builtin_amdgcn_exp2f(v.x - mrow);
+      }
+      lse_s[lane] = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;   // no visible key: all scores 0
+    }
+    __syncthreads();
+    bm0 = a.fs.bmax + (head * a.fs.bm_rows + (int64_t)i * 8) * a.fs.bm_pitch;
+  }
+  // FACTORED: the row's scores, block c*64 + lane in element c.  All loads first (8 rows x KPL per
+  // lane, no store in between for the compiler to order them against), then the optional write-out.
+  float sc[KPL];
+  if (FACTORED) {
+#pragma unroll
+    for (int c = 0; c < KPL; ++c) sc[c] = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float* __restrict__ br = bm0 + (int64_t)r * a.fs.bm_pitch;
+      const float lr = lse_s[r];
+#pragma unroll
+      for (int c = 0; c < KPL; ++c) {
+        const int j = c * 64 + lane;
+        if (j < a.nk) sc[c] = fmaxf(sc[c], br[j] - lr);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < KPL; ++c) sc[c] = __builtin_amdgcn_exp2f(sc[c]);
+    if (a.S_out) {
+#pragma unroll
+      for (int c = 0; c < KPL; ++c) {
+        const int j = c * 64 + lane;
+        if (j < a.nk) a.S_out[row * a.nk + j] = sc[c];
+      }
+    }
+  }
   uint8_t* m_row = M + row * a.nk;
   const uint8_t* cap_row = cap ? cap + ((int64_t)b * a.Hkv + hq / (a.Hq / a.Hkv)) * a.nk : nullptr;
   const bool quota = a.mode != PSA_ALLOC_THRESHOLD;
@@ -96,10 +144,11 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
     uint64_t kk = ~0ull;
     if (j < a.nk) {
       const int v = block_vis(i, j, a.bq, a.bk, a.N, a.causal);
+      const float sj = FACTORED ? sc[r] : (v != 0 ? s_row[j] : 0.f);
       if (v == 0) {
         m_row[j] = 0;
       } else {
-        const uint32_t ord = (quota && v == 2) ? 0u : desc_bits(s_row[j]);
+        const uint32_t ord = (quota && v == 2) ? 0u : desc_bits(sj);
         kk = ((uint64_t)ord << 32) | (uint32_t)j;
         ++n_vis;
       }
@@ -218,13 +267,18 @@ template <int KPL>
 static hipError_t launch_alloc_t(const Plan& pl, const AllocArgs& a, const float* S, const uint8_t* cap, uint8_t* M,
                                  uint32_t* rowcnt, hipStream_t s) {
   dim3 grid(pl.nq, pl.Hq, pl.B);
-  alloc_kernel<KPL><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
+  if (a.fs.bmax) alloc_kernel<KPL, true><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
+  else alloc_kernel<KPL, false><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
   return hipGetLastError();
 }
 
-hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, uint8_t* M, uint32_t* rowcnt,
-                           hipStream_t s) {
+hipError_t launch_allocate(const Plan& pl, const float* S, const FactoredScores* factored, float* S_out,
+                           const uint8_t* cap, uint8_t* M, uint32_t* rowcnt, hipStream_t s) {
   AllocArgs a;
+  if (factored) a.fs = *factored;
+  else { a.fs.part = nullptr; a.fs.bmax = nullptr; a.fs.ksplit = 0; a.fs.bm_rows = 0; a.fs.bm_pitch = 0; }
+  a.S_out = factored ? S_out : nullptr;
+
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.H = pl.H; a.causal = pl.causal; a.mode = pl.alloc_mode;
   for (int h = 0; h < PSA_MAX_LEVELS; ++h) { a.tau[h] = pl.tau[h]; a.cuts[h] = pl.cuts[h]; }

@@ -171,30 +171,36 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
   if (reinterpret_cast<uintptr_t>(scratch) & 255) return PSA_EINVAL;
   if (pl.nk > PSA_MAX_NK) return PSA_EUNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const float* scores = scores_in;
-  if (!scores_in) {
-    if (!Q) return PSA_EINVAL;
-    if (pl.krep_is_pyramid ? !Kpyr : !K) return PSA_EINVAL;
-    if (!importance_uses_mfma(pl) && importance_smem_bytes(pl.sq, pl.nk, pl.d) > LDS_LIMIT) return PSA_EUNSUPPORTED;
-    void* qrep = at(scratch, pl.off_qrep);
-    const void* krep;
-    if (launch_representatives(pl, Q, qrep, true, s) != hipSuccess) return PSA_ELAUNCH;
-    if (pl.krep_is_pyramid) {
-      krep = static_cast<const char*>(Kpyr) + (size_t)pl.lvl_off[pl.H] * pl.esize;
-    } else {
-      void* kr = at(scratch, pl.off_krep);
-      if (launch_representatives(pl, K, kr, false, s) != hipSuccess) return PSA_ELAUNCH;
-      krep = kr;
-    }
-    float* sdst = scores_out ? scores_out : reinterpret_cast<float*>(at(scratch, pl.off_scores));
-    if (launch_importance(pl, qrep, krep, at(scratch, pl.off_part), at(scratch, pl.off_bmax), sdst, s) != hipSuccess) return PSA_ELAUNCH;
-    scores = sdst;
-  } else if (scores_out && scores_out != scores_in) {
-    const size_t bytes = (size_t)pl.B * pl.Hq * pl.nq * pl.nk * sizeof(float);
-    if (hipMemcpyAsync(scores_out, scores_in, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return PSA_ELAUNCH;
-  }
   uint32_t* rowcnt = reinterpret_cast<uint32_t*>(at(scratch, pl.off_rowcnt));
-  if (launch_allocate(pl, scores, level_cap, M, rowcnt, s) != hipSuccess) return PSA_ELAUNCH;
+  if (scores_in) {
+    if (scores_out && scores_out != scores_in) {
+      const size_t bytes = (size_t)pl.B * pl.Hq * pl.nq * pl.nk * sizeof(float);
+      if (hipMemcpyAsync(scores_out, scores_in, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return PSA_ELAUNCH;
+    }
+    if (launch_allocate(pl, scores_in, nullptr, nullptr, level_cap, M, rowcnt, s) != hipSuccess) return PSA_ELAUNCH;
+    if (rho_out && launch_rho(pl, rowcnt, rho_out, s) != hipSuccess) return PSA_ELAUNCH;
+    return PSA_OK;
+  }
+  if (!Q) return PSA_EINVAL;
+  if (pl.krep_is_pyramid ? !Kpyr : !K) return PSA_EINVAL;
+  if (!importance_uses_mfma(pl) && importance_smem_bytes(pl.sq, pl.nk, pl.d) > LDS_LIMIT) return PSA_EUNSUPPORTED;
+  void* qrep = at(scratch, pl.off_qrep);
+  const void* krep;
+  if (launch_representatives(pl, Q, qrep, true, s) != hipSuccess) return PSA_ELAUNCH;
+  if (pl.krep_is_pyramid) {
+    krep = static_cast<const char*>(Kpyr) + (size_t)pl.lvl_off[pl.H] * pl.esize;
+  } else {
+    void* kr = at(scratch, pl.off_krep);
+    if (launch_representatives(pl, K, kr, false, s) != hipSuccess) return PSA_ELAUNCH;
+    krep = kr;
+  }
+  float* sdst = scores_out ? scores_out : reinterpret_cast<float*>(at(scratch, pl.off_scores));
+  FactoredScores fs;
+  fs.bmax = nullptr;
+  if (launch_importance(pl, qrep, krep, at(scratch, pl.off_part), at(scratch, pl.off_bmax), sdst, &fs, s) != hipSuccess) return PSA_ELAUNCH;
+  const bool factored = fs.bmax != nullptr;
+  if (launch_allocate(pl, factored ? nullptr : sdst, factored ? &fs : nullptr, factored ? scores_out : nullptr, level_cap, M,
+                      rowcnt, s) != hipSuccess) return PSA_ELAUNCH;
   if (rho_out && launch_rho(pl, rowcnt, rho_out, s) != hipSuccess) return PSA_ELAUNCH;
   return PSA_OK;
 }

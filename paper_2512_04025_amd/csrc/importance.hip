@@ -228,9 +228,11 @@ static hipError_t launch_imp_t(const Plan& pl, const void* Qrep, const void* Kre
 // tiles, shared by the four wavefronts, chunks XOR-swizzled as in the attention kernel) and
 // S^T = K~ Q~^T runs on 32x32x16 MFMAs with one query row per lane.
 //   sweep 1: per row and key slice, the running maximum and the sum of exponentials (log2 domain)
-//   sweep 2: the slices' partial results merged into lse = m + log2(l) per row; the logits are
-//            recomputed and w = 2^(scale*dot - lse) is pooled over every 8x8 sub-tile.  For max
-//            pooling the monotone exp2 is applied once, after the maximum.
+//            and, for max pooling, the largest logit of every (row, key block): exp2 is monotone, so
+//            S_ij = 2^(max over the block pair's 8x8 logits - lse) needs no second sweep; the allocation
+//            kernel evaluates that while it loads its row of scores
+//   sweep 2  (mean pooling only): the slices' partial results merged into lse = m + log2(l) per row;
+//            the logits are recomputed and w = 2^(scale*dot - lse) is averaged over every 8x8 sub-tile
 // Cross-lane steps use the half-swap and lane-permuting operands instead of LDS shuffles.
 constexpr int IMP_MAX_SPLIT = 8;
 
@@ -637,36 +639,9 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
   }
 }
 
-// Second pass for max pooling: S[i, j] = 2^(max over the 8 rows of block i of (block maximum - lse of the row)).
-__global__ __launch_bounds__(256) void importance_finalize_kernel(const float2* __restrict__ part,
-                                                                  const float* __restrict__ bmax, float* __restrict__ S,
-                                                                  int nq, int nk, int ksplit, int bm_rows, int bm_pitch) {
-  __shared__ float lse_s[8];
-  const int tid = threadIdx.x, qi = blockIdx.x, head = blockIdx.y;
-  const int nrows = nq * 8;
-  if (tid < 8) {
-    const float2* pr = part + ((int64_t)head * nrows + qi * 8 + tid) * IMP_MAX_SPLIT;
-    float mrow = -INFINITY, lrow = 0.f;
-    for (int s2 = 0; s2 < ksplit; ++s2) mrow = fmaxf(mrow, pr[s2].x);
-    for (int s2 = 0; s2 < ksplit; ++s2) {
-      const float2 v = pr[s2];
-      if (v.x != -INFINITY) lrow += v.y * __builtin_amdgcn_exp2f(v.x - mrow);
-    }
-    lse_s[tid] = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;
-  }
-  __syncthreads();
-  const float* b0 = bmax + ((int64_t)head * bm_rows + qi * 8) * bm_pitch;
-  for (int j = tid; j < nk; j += 256) {
-    float v = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) v = fmaxf(v, b0[(int64_t)r * bm_pitch + j] - lse_s[r]);
-    S[((int64_t)head * nq + qi) * nk + j] = __builtin_amdgcn_exp2f(v);
-  }
-}
-
 template <int D>
 static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const void* Krep, float2* part, float* bmax,
-                                     float* S, hipStream_t s) {
+                                     float* S, FactoredScores* factored, hipStream_t s) {
   ImpTileArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.mode = pl.rep_mode; a.causal = pl.causal; a.est_pool = pl.est_pool;
@@ -703,10 +678,10 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
                              keep_max ? bmax : nullptr, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (keep_max) {
-    importance_finalize_kernel<<<dim3(pl.nq, pl.Hq * pl.B), 256, 0, s>>>(part, bmax, S, pl.nq, pl.nk, ksplit, a.bm_rows,
-                                                                         a.bm_pitch);
-    return hipGetLastError();
+  if (keep_max) {   // the second pass is elementwise: the allocation kernel does it while it loads its row
+    factored->part = part; factored->bmax = bmax;
+    factored->ksplit = ksplit; factored->bm_rows = a.bm_rows; factored->bm_pitch = a.bm_pitch;
+    return hipSuccess;
   }
   k2<<<grid, 256, smem, s>>>(static_cast<const bf16_t*>(Qrep), static_cast<const bf16_t*>(Krep), part, S, nullptr, a);
   return hipGetLastError();
@@ -715,10 +690,11 @@ static hipError_t launch_imp_tiles_t(const Plan& pl, const void* Qrep, const voi
 bool importance_uses_mfma(const Plan& pl) { return pl.dtype == PSA_BF16 && pl.sq == 8 && pl.sk == 8; }
 
 hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, void* bmax, float* S,
-                             hipStream_t s) {
+                             FactoredScores* factored, hipStream_t s) {
+  factored->bmax = nullptr;
   if (importance_uses_mfma(pl))
-    return pl.d == 64 ? launch_imp_tiles_t<64>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, s)
-                      : launch_imp_tiles_t<128>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, s);
+    return pl.d == 64 ? launch_imp_tiles_t<64>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, factored, s)
+                      : launch_imp_tiles_t<128>(pl, Qrep, Krep, static_cast<float2*>(part), static_cast<float*>(bmax), S, factored, s);
   if (pl.dtype == PSA_F32)
     return pl.d == 64 ? launch_imp_t<float, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<float, 128>(pl, Qrep, Krep, S, s);
   return pl.d == 64 ? launch_imp_t<bf16_t, 64>(pl, Qrep, Krep, S, s) : launch_imp_t<bf16_t, 128>(pl, Qrep, Krep, S, s);

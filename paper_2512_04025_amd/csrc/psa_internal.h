@@ -42,14 +42,30 @@ constexpr int ROWCNT_STRIDE = PSA_MAX_LEVELS + 1;
 // per-row level counts consumed by the attention kernels: c_1 .. c_H
 constexpr int CNT_STRIDE = PSA_MAX_LEVELS;
 
+// Scores in the factored form the matrix-core importance sweep leaves behind (max pooling): per
+// representative query row the softmax statistics (maximum, sum of exponentials, log2 domain) of every
+// key slice, and per (representative row, key block) the largest logit.  The score of block pair
+// (i, j) is 2^(max over the 8 rows r of block i of (bmax[r, j] - lse[r])).
+struct FactoredScores {
+  const float2* part;      // [heads][nq * 8][8 slices]
+  const float* bmax;       // [heads][bm_rows][bm_pitch]
+  int ksplit, bm_rows, bm_pitch;
+};
+
 hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s);
 hipError_t launch_representatives(const Plan& pl, const void* X, void* R, bool is_query, hipStream_t s);
 // part: per (row, key slice) partial softmax statistics of the matrix-core path (Plan::off_part)
 // bmax: per (representative row, key block) largest logit, kept for max pooling (Plan::off_bmax)
+// factored (nullable out): when the scores can stay in factored form it is filled in, S is NOT written
+// and the allocation kernel evaluates the scores itself; otherwise factored->bmax is left null and S holds the scores
 hipError_t launch_importance(const Plan& pl, const void* Qrep, const void* Krep, void* part, void* bmax, float* S,
-                             hipStream_t s);
-hipError_t launch_allocate(const Plan& pl, const float* S, const uint8_t* cap, uint8_t* M, uint32_t* rowcnt,
-                           hipStream_t s);
+                             FactoredScores* factored, hipStream_t s);
+// Scores come from S, or (factored != null) are evaluated from the factored form and, if S_out is given,
+// written there as well.  rowcnt: per-row counters [n_visible, c_1..c_H] for launch_rho.
+// (Eq. 9 per head stays a kernel of its own: summing the rows' counters with atomics from the allocation
+// kernel's 256+ workgroups per head onto a handful of addresses was measured 70 us slower than that 4 us kernel.)
+hipError_t launch_allocate(const Plan& pl, const float* S, const FactoredScores* factored, float* S_out,
+                           const uint8_t* cap, uint8_t* M, uint32_t* rowcnt, hipStream_t s);
 hipError_t launch_rho(const Plan& pl, const uint32_t* rowcnt, float* rho, hipStream_t s);
 hipError_t launch_schedule(const Plan& pl, const uint8_t* M, uint16_t* idx, int32_t* cnt, hipStream_t s);
 // Per query block and 64-column tile of its level-sorted block list: source-row offsets of the tile's

@@ -452,3 +452,80 @@ def test_executed_flops_is_rho_times_dense_on_whole_blocks():
     M = np.random.default_rng(8).integers(0, 5, size=(2, 3, p.nq, p.nk)).astype(np.uint8)
     rho = orc.compute_ratio(M, p).sum()
     assert orc.executed_flops(M, p) == pytest.approx(rho * 4 * 256 * 256 * 16, rel=1e-12)
+
+
+# ---------------------------------------------------------------- App. B.1 / Alg. 3: similarity cap
+def test_similarity_cap_identities_stated_in_the_paper():
+    """All thresholds -1 disable the constraint (L = H everywhere); all thresholds 1 force L = 1."""
+    p = Params(2, 2, 2, 150, 8, 32, 32, 4)          # ragged last block of 22 tokens
+    K = _rand(60, 2, 2, 150, 8)
+    for reduce in ("per_head", "all_heads"):
+        L, _ = orc.similarity_level_cap(K, p, (-1.0, -1.0, -1.0), reduce)
+        assert np.all(L == 4)
+        L, _ = orc.similarity_level_cap(K, p, (1.0, 1.0, 1.0), reduce)
+        assert np.all(L == 1)
+
+
+def test_similarity_of_identical_keys_is_one_and_scale_free():
+    p = Params(1, 1, 1, 64, 6, 16, 16, 3)
+    K = np.repeat(_rand(61, 1, 1, 4, 6), 16, axis=2)                     # every block: one key repeated
+    _, sims = orc.similarity_level_cap(K, p, (0.5, 0.5))
+    np.testing.assert_allclose(sims, 1.0, rtol=0, atol=1e-12)
+    K2 = _rand(62, 1, 1, 64, 6)
+    gains = np.random.default_rng(1).uniform(0.1, 9.0, size=(1, 1, 64, 1))
+    np.testing.assert_allclose(orc.block_similarities(K2 * gains, p), orc.block_similarities(K2, p), atol=1e-12)
+
+
+def test_similarity_cap_planar_example_by_hand():
+    """One block of 8 unit vectors in the plane at angles 0, 15, ... 105 degrees: every stride-2 pair is
+    30 degrees apart (cos = sqrt(3)/2), every stride-4 pair 60 degrees (cos = 1/2).  With thresholds
+    (0.9, 0.4) level 2 fails and level 3 passes: Alg. 3 tests every level, so L = 3."""
+    ang = np.deg2rad(15.0 * np.arange(8))
+    K = np.stack([np.cos(ang), np.sin(ang)], axis=1)[None, None]
+    p = Params(1, 1, 1, 8, 2, 8, 8, 3)
+    L, sims = orc.similarity_level_cap(K, p, (0.7, 0.6))
+    np.testing.assert_allclose(sims[0, 0, 0], [math.sqrt(3) / 2, 0.5], atol=1e-12)
+    assert L[0, 0, 0] == 2
+    assert orc.similarity_level_cap(K, p, (0.9, 0.4))[0][0, 0, 0] == 3
+    assert orc.similarity_level_cap(K, p, (0.9, 0.6))[0][0, 0, 0] == 1
+    # antiparallel neighbours at stride 2: cos = -1
+    K2 = np.array([[1.0, 0], [0, 1.0], [-1.0, 0], [0, -1.0]] * 2)[None, None]
+    np.testing.assert_allclose(orc.block_similarities(K2, p)[0, 0, 0], [-1.0, 1.0], atol=1e-12)
+
+
+@pytest.mark.parametrize("N", [64, 53])
+def test_similarity_cap_matches_loop_brute_force(N):
+    p = Params(2, 2, 2, N, 5, 16, 16, 4)
+    K = _rand(63, 2, 2, N, 5)
+    K[0, 1, 7] = 0.0                                                      # a zero key: its pairs count as 0
+    sims = orc.block_similarities(K, p)
+    for b in range(2):
+        for hk in range(2):
+            for j in range(p.nk):
+                for h in (2, 3, 4):
+                    s, vals = 1 << (h - 1), []
+                    for t in range(j * 16, min((j + 1) * 16, N)):
+                        u = t + s
+                        if u < min((j + 1) * 16, N):
+                            na, nb = math.sqrt(sum(x * x for x in K[b, hk, t])), math.sqrt(sum(x * x for x in K[b, hk, u]))
+                            dot = sum(x * y for x, y in zip(K[b, hk, t], K[b, hk, u]))
+                            vals.append(dot / max(na * nb, 1e-8))
+                    want = sum(vals) / len(vals) if vals else 1.0
+                    assert abs(sims[b, hk, j, h - 2] - want) < 1e-12
+    Lp, _ = orc.similarity_level_cap(K, p, (0.1, 0.0, -0.1), "per_head")
+    La, _ = orc.similarity_level_cap(K, p, (0.1, 0.0, -0.1), "all_heads")
+    mean = sims.mean(axis=(0, 1))
+    for j in range(p.nk):
+        want = max([1] + [h for h, t in zip((2, 3, 4), (0.1, 0.0, -0.1)) if mean[j, h - 2] > np.float32(t)])
+        assert np.all(La[:, :, j] == want)
+    assert Lp.shape == (2, 2, p.nk) and set(np.unique(Lp)) <= {1, 2, 3, 4}
+
+
+def test_similarity_cap_feeds_the_allocation():
+    """M~ = min(M, L) on kept blocks (App. B.1): the cap from Alg. 3 through allocate_levels."""
+    p = Params(1, 2, 1, 128, 8, 16, 16, 4, alloc_mode="budget", budget=0.5)
+    Q, K = _rand(64, 1, 2, 128, 8), _rand(65, 1, 1, 128, 8)
+    L, _ = orc.similarity_level_cap(K, p, (0.05, 0.0, -0.05))
+    S = orc.importance(Q, K, p)
+    M, Mc = orc.allocate_levels(S, p), orc.allocate_levels(S, p, level_cap=L)
+    assert np.array_equal(Mc, np.where(M > 0, np.minimum(M, L[:, :1]), 0))
