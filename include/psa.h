@@ -3,6 +3,7 @@
  *
  * The four calls are the stages of the method in "PSA: Pyramid Sparse Attention":
  *   psa_build_pyramid    Sec. 3.2, Eq. 2-3   mean-pooled K/V pyramid
+ *   psa_level_cap        App. B.1, Alg. 3    optional cosine-similarity cap on the level of a key block
  *   psa_allocate_levels  Sec. 3.3, Eq. 4, Alg. 2, Eq. 5-7 (+ the quantile rule of Sec. 4.4)
  *   psa_attention_fwd    Sec. 3.4, Alg. 1, Eq. 8   online-softmax attention over mixed-level KV blocks
  *   psa_dense_ref        Sec. 3.1, Eq. 1     plain softmax attention (reference / comparison)
@@ -38,6 +39,7 @@ enum { PSA_BF16 = 0, PSA_F32 = 1 };
 enum { PSA_REP_STRIDED = 0, PSA_REP_POOLED = 1 };
 enum { PSA_EST_MAX = 0, PSA_EST_MEAN = 1 };
 enum { PSA_ALLOC_THRESHOLD = 0, PSA_ALLOC_QUANTILE = 1, PSA_ALLOC_BUDGET = 2 };
+enum { PSA_CAP_PER_HEAD = 0, PSA_CAP_ALL_HEADS = 1 };
 
 #define PSA_MAX_LEVELS 8
 #define PSA_MAX_NK 4096 /* key blocks per row the allocation kernel can sort */
@@ -82,6 +84,33 @@ int psa_query_sizes(const psa_params* p, size_t* pyr_bytes, size_t* scratch_byte
  */
 int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* Kpyr, void* Vpyr,
                       void* stream);
+
+/*
+ * Cosine-similarity pooling constraint, App. B.1 / Alg. 3: the maximum admissible level of every key
+ * block.  sim_h(j), h = 2..H, is the mean cosine similarity of the token pairs of key block j that lie
+ * 2^(h-1) apart (both tokens inside the block and the sequence; a pair's cosine is
+ * dot / max(|a| |b|, 1e-8); a block holding no such pair gets sim_h = 1);  L_j = 1, and for every
+ * h = 2..H:  if sim_h(j) > tau_s[h-2] then L_j = max(L_j, h).  The result is the level_cap input of
+ * psa_allocate_levels (final mask min(M, L) on kept blocks).
+ *   tau_s   HOST pointer, H-1 thresholds in [-1, 1] for levels 2..H (all -1: L = H everywhere, the
+ *           constraint is off; all 1: L = 1 everywhere).  Read during the call.
+ *   reduce  PSA_CAP_PER_HEAD: one L per (batch, key head), sim_h from that head's keys;
+ *           PSA_CAP_ALL_HEADS: sim_h(j) is also averaged over batch and key heads (Alg. 3 views a block
+ *           as a [B, heads, b_k, d] tensor and returns one L per block); every (batch, head) gets that L
+ *   sim     out, float [B, Hkv, nk, H-1]: the per-head similarities (NULL allowed only when H = 1)
+ *   L       out, uint8 [B, Hkv, nk], values 1..H
+ * psa_level_cap reads K once.  psa_build_pyramid_cap is psa_build_pyramid that also produces sim and L in
+ * the same pass over K: when the keys of a block are handled by one workgroup of the pooling kernel
+ * (16-byte chunks per row x b_k / 2^(H-1) divides 256: every benchmark shape) the block's rows are
+ * reduced right after they were streamed, from cache; other shapes run the reduction as a second kernel.
+ * Arithmetic: dot products and norms in fp32, the mean in fp64 in a fixed order (deterministic).
+ * Errors: PSA_EINVAL (null pointer, threshold outside [-1, 1], unknown reduce), PSA_EUNSUPPORTED
+ *         (b_k > 8192), PSA_ELAUNCH.
+ */
+int psa_level_cap(const psa_params* p, const void* K, const float* tau_s, int reduce, float* sim,
+                  uint8_t* L, void* stream);
+int psa_build_pyramid_cap(const psa_params* p, const void* K, const void* V, void* Kpyr, void* Vpyr,
+                          const float* tau_s, int reduce, float* sim, uint8_t* L, void* stream);
 
 /*
  * Multi-level mask generator, Sec. 3.3.

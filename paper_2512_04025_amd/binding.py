@@ -10,6 +10,7 @@ PSA_BF16, PSA_F32 = 0, 1
 PSA_REP_STRIDED, PSA_REP_POOLED = 0, 1
 PSA_EST_MAX, PSA_EST_MEAN = 0, 1
 PSA_ALLOC_THRESHOLD, PSA_ALLOC_QUANTILE, PSA_ALLOC_BUDGET = 0, 1, 2
+PSA_CAP_PER_HEAD, PSA_CAP_ALL_HEADS = 0, 1
 PSA_MAX_LEVELS = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -61,6 +62,9 @@ def load_library() -> ctypes.CDLL:
     szp = ctypes.POINTER(ctypes.c_size_t)
     lib.psa_query_sizes.argtypes = [pp, szp, szp]
     lib.psa_build_pyramid.argtypes = [pp, vp, vp, vp, vp, vp]
+    fp = ctypes.POINTER(ctypes.c_float)
+    lib.psa_level_cap.argtypes = [pp, vp, fp, ctypes.c_int, vp, vp, vp]
+    lib.psa_build_pyramid_cap.argtypes = [pp, vp, vp, vp, vp, fp, ctypes.c_int, vp, vp, vp]
     lib.psa_allocate_levels.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -70,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
     for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_attention_fwd_static",
+                 "psa_level_cap", "psa_build_pyramid_cap",
                  "psa_dense_ref", "psa_probe_copy", "psa_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -126,6 +131,25 @@ def psa_query_sizes(p: PsaParams) -> Tuple[int, int]:
 def psa_build_pyramid(p: PsaParams, K, V, Kpyr, Vpyr, stream=None) -> None:
     _check(load_library().psa_build_pyramid(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(Kpyr), _ptr(Vpyr),
                                             _stream(stream)), "psa_build_pyramid")
+
+
+def _thresholds(p: PsaParams, tau_s: Sequence[float]):
+    vals = list(tau_s)
+    if len(vals) < p.levels - 1:
+        raise ValueError("need levels - 1 similarity thresholds")
+    return (ctypes.c_float * max(len(vals), 1))(*vals)
+
+
+def psa_level_cap(p: PsaParams, K, tau_s: Sequence[float], sim, L, reduce: int = PSA_CAP_PER_HEAD, stream=None) -> None:
+    _check(load_library().psa_level_cap(ctypes.byref(p), _ptr(K), _thresholds(p, tau_s), ctypes.c_int(reduce),
+                                        _ptr(sim), _ptr(L), _stream(stream)), "psa_level_cap")
+
+
+def psa_build_pyramid_cap(p: PsaParams, K, V, Kpyr, Vpyr, tau_s: Sequence[float], sim, L,
+                          reduce: int = PSA_CAP_PER_HEAD, stream=None) -> None:
+    _check(load_library().psa_build_pyramid_cap(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(Kpyr), _ptr(Vpyr),
+                                                _thresholds(p, tau_s), ctypes.c_int(reduce), _ptr(sim), _ptr(L),
+                                                _stream(stream)), "psa_build_pyramid_cap")
 
 
 def psa_allocate_levels(p: PsaParams, Q, K, Kpyr, M, scratch, scores_in=None, scores_out=None,

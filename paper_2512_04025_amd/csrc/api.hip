@@ -156,7 +156,50 @@ int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* K
   if (rc != PSA_OK) return rc;
   if (pl.H == 1) return PSA_OK;
   if (!K || !V || !Kpyr || !Vpyr) return PSA_EINVAL;
-  return launch_pyramid(pl, K, V, Kpyr, Vpyr, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+  return launch_pyramid(pl, K, V, Kpyr, Vpyr, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
+static int check_cap_args(const Plan& pl, const float* tau_s, int reduce, const float* sim, const uint8_t* L) {
+  if (!L || (reduce != PSA_CAP_PER_HEAD && reduce != PSA_CAP_ALL_HEADS)) return PSA_EINVAL;
+  if (pl.H > 1 && (!tau_s || !sim)) return PSA_EINVAL;
+  for (int h = 0; h < pl.H - 1; ++h)
+    if (!(tau_s[h] >= -1.f) || !(tau_s[h] <= 1.f)) return PSA_EINVAL;
+  if (pl.bk > 8192) return PSA_EUNSUPPORTED;   // the norms of one key block are kept in LDS
+  return PSA_OK;
+}
+
+// H = 1 has no pooled level to cap: L = 1 everywhere (a fill kernel, not a memset node: see the header)
+static hipError_t cap_all_ones(const Plan& pl, uint8_t* L, hipStream_t s) {
+  const float none[1] = {0.f};
+  return launch_level_cap(pl, nullptr, none, false, L, s);
+}
+
+int psa_level_cap(const psa_params* p, const void* K, const float* tau_s, int reduce, float* sim, uint8_t* L,
+                  void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  rc = check_cap_args(pl, tau_s, reduce, sim, L);
+  if (rc != PSA_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (pl.H == 1) return cap_all_ones(pl, L, s) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+  if (!K) return PSA_EINVAL;
+  if (launch_similarities(pl, K, sim, s) != hipSuccess) return PSA_ELAUNCH;
+  return launch_level_cap(pl, sim, tau_s, reduce == PSA_CAP_ALL_HEADS, L, s) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
+int psa_build_pyramid_cap(const psa_params* p, const void* K, const void* V, void* Kpyr, void* Vpyr,
+                          const float* tau_s, int reduce, float* sim, uint8_t* L, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  rc = check_cap_args(pl, tau_s, reduce, sim, L);
+  if (rc != PSA_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (pl.H == 1) return cap_all_ones(pl, L, s) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+  if (!K || !V || !Kpyr || !Vpyr) return PSA_EINVAL;
+  if (launch_pyramid(pl, K, V, Kpyr, Vpyr, sim, s) != hipSuccess) return PSA_ELAUNCH;
+  return launch_level_cap(pl, sim, tau_s, reduce == PSA_CAP_ALL_HEADS, L, s) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 
 int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const void* Kpyr,

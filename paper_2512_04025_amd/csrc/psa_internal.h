@@ -52,7 +52,11 @@ struct FactoredScores {
   int ksplit, bm_rows, bm_pitch;
 };
 
-hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s);
+// sims (nullable): also write the intra-block cosine similarities of Alg. 3, float [B*Hkv][nk][H-1]
+hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, float* sims, hipStream_t s);
+hipError_t launch_similarities(const Plan& pl, const void* K, float* sims, hipStream_t s);
+// tau_s: host, H-1 thresholds for levels 2..H; L: uint8 [B*Hkv][nk]
+hipError_t launch_level_cap(const Plan& pl, const float* sims, const float* tau_s, bool all_heads, uint8_t* L, hipStream_t s);
 hipError_t launch_representatives(const Plan& pl, const void* X, void* R, bool is_query, hipStream_t s);
 // part: per (row, key slice) partial softmax statistics of the matrix-core path (Plan::off_part)
 // bmax: per (representative row, key block) largest logit, kept for max pooling (Plan::off_bmax)

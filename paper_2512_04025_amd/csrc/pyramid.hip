@@ -5,6 +5,12 @@
 // level and emits a pooled token whenever its span closes, so level 1 is read exactly once and each
 // pooled level is written exactly once.  Algorithmic bytes per (token, channel, tensor):
 // e * (1 + sum_{h=2..H} 2^-(h-1)), e = element size.
+//
+// The same pass can also produce the intra-block cosine similarities of App. B.1 / Alg. 3
+// (sim_h(j), h = 2..H: mean cosine of the token pairs of key block j that lie 2^(h-1) apart): when a
+// workgroup's tokens are whole key blocks it re-reads the K rows it has just streamed (cache hits, no
+// further HBM traffic) and reduces them; other shapes run the same reduction as a kernel of its own.
+// cap_kernel then turns the similarities into the per-block maximum level L.
 #include "psa_dev.h"
 #include "psa_internal.h"
 
@@ -18,18 +24,78 @@ struct PyrArgs {
   int64_t lvl_off[PSA_MAX_LEVELS + 2];
 };
 
+struct SimArgs {
+  float* sims;           // out [heads][nk][H-1]; nullptr: no similarities wanted
+  int H;
+};
+
+constexpr float COS_EPS = 1e-8f;   // cosine = dot / max(|a| |b|, COS_EPS): a zero key gives 0
+constexpr int SIM_MAX_TEAMS = 32;
+
+// sim_h(j), h = 2..H, of ONE key block (Alg. 3), by all `nthreads` threads of a workgroup.  A team of
+// `chunks` lanes (one 16-byte chunk of a row each) handles one token pair at a time; a team sums its
+// cosines in double, the teams' sums are added in a fixed order: the result does not depend on timing.
+// Reading: pairs (t, t + 2^(h-1)) with both tokens inside the block and the sequence; a block without
+// such a pair gets 1.  lds: bk floats (norms) followed by SIM_MAX_TEAMS * PSA_MAX_LEVELS doubles.
+template <typename T>
+__device__ void block_sims(const T* __restrict__ khead, int j, int N, int d, int bk, int H, int chunks,
+                           float* __restrict__ out, unsigned char* lds, int tid, int nthreads) {
+  constexpr int VEC = Elem<T>::VEC;
+  float* nrm = reinterpret_cast<float*>(lds);
+  double* part = reinterpret_cast<double*>(lds + (((size_t)bk * sizeof(float) + 15) & ~(size_t)15));
+  const int teams = nthreads / chunks, team = tid / chunks, tl = tid % chunks;
+  const int lo = j * bk;
+  int ntok = N - lo;
+  ntok = ntok > bk ? bk : ntok;
+  auto team_sum = [&](float x) __attribute__((always_inline)) {
+    for (int off = chunks >> 1; off; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+  };
+  __syncthreads();                               // LDS may still be in use by the previous block
+  for (int t = team; t < ntok; t += teams) {
+    float a[VEC];
+    Elem<T>::load(khead + (int64_t)(lo + t) * d + tl * VEC, a);
+    float acc = 0.f;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc = fmaf(a[e], a[e], acc);
+    acc = team_sum(acc);
+    if (tl == 0) nrm[t] = sqrtf(acc);
+  }
+  __syncthreads();
+  for (int h = 2; h <= H; ++h) {
+    const int s = 1 << (h - 1);
+    double sum = 0.0;
+    for (int t = team; t + s < ntok; t += teams) {
+      float a[VEC], b[VEC];
+      Elem<T>::load(khead + (int64_t)(lo + t) * d + tl * VEC, a);
+      Elem<T>::load(khead + (int64_t)(lo + t + s) * d + tl * VEC, b);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc = fmaf(a[e], b[e], acc);
+      acc = team_sum(acc);
+      sum += (double)(acc / fmaxf(nrm[t] * nrm[t + s], COS_EPS));
+    }
+    if (tl == 0) part[team * PSA_MAX_LEVELS + (h - 2)] = sum;
+  }
+  __syncthreads();
+  if (tid < H - 1) {
+    const int s = 1 << (tid + 1);
+    const int npairs = ntok - s;
+    double tot = 0.0;
+    for (int t = 0; t < teams; ++t) tot += part[t * PSA_MAX_LEVELS + tid];
+    out[tid] = npairs > 0 ? (float)(tot / (double)npairs) : 1.f;
+  }
+}
+
 template <typename T> struct AccOf { typedef float type; };
 template <> struct AccOf<float> { typedef double type; };
 
 template <typename T, int H>
-__global__ __launch_bounds__(256) void pyramid_kernel(const T* __restrict__ K, const T* __restrict__ V,
-                                                      T* __restrict__ Kp, T* __restrict__ Vp, PyrArgs a) {
+__device__ __forceinline__ void pyramid_body(const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ Kp,
+                                             T* __restrict__ Vp, const PyrArgs& a, int64_t gid) {
   constexpr int G = 1 << (H - 1);
   constexpr int VEC = Elem<T>::VEC;
   constexpr int BATCH = G < 8 ? G : 8;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t total = (int64_t)a.heads * a.groups * a.chunks;
-  if (gid >= total) return;
   const int c = (int)(gid % a.chunks);
   const int g = (int)((gid / a.chunks) % a.groups);
   const int bh = (int)(gid / ((int64_t)a.chunks * a.groups));
@@ -93,8 +159,78 @@ __global__ __launch_bounds__(256) void pyramid_kernel(const T* __restrict__ K, c
   }
 }
 
+// SIMS: the workgroup's 256 threads cover whole key blocks (256 is a multiple of the threads per block,
+// chunks * bk / 2^(H-1)); after its part of the pyramid the K half also reduces their similarities.
+template <typename T, int H, bool SIMS>
+__global__ __launch_bounds__(256) void pyramid_kernel(const T* __restrict__ K, const T* __restrict__ V,
+                                                      T* __restrict__ Kp, T* __restrict__ Vp, PyrArgs a, SimArgs sa) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sim_lds[];
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)a.heads * a.groups * a.chunks;
+  if (SIMS && blockIdx.y == 0) {
+    // (no thread of such a workgroup may leave before the barriers below: the tail of the grid included)
+    if (gid < total) pyramid_body<T, H>(K, V, Kp, Vp, a, gid);
+    const int tpb = a.chunks * (a.bk >> (H - 1));            // threads per key block
+    const int64_t first = (int64_t)blockIdx.x * (256 / tpb);  // first (head, block) pair of this workgroup
+    for (int x = 0; x < 256 / tpb; ++x) {
+      const int64_t hb = first + x;
+      if (hb >= (int64_t)a.heads * a.nk) break;              // uniform over the workgroup
+      const int bh = (int)(hb / a.nk), j = (int)(hb % a.nk);
+      block_sims<T>(K + (int64_t)bh * a.N * a.d, j, a.N, a.d, a.bk, H, a.chunks,
+                    sa.sims + hb * (H - 1), sim_lds, (int)threadIdx.x, 256);
+    }
+    return;
+  }
+  if (gid >= total) return;
+  pyramid_body<T, H>(K, V, Kp, Vp, a, gid);
+}
+
 template <typename T>
-static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s) {
+static hipError_t launch_sims_t(const Plan& pl, const void* K, float* sims, hipStream_t s);
+
+// The similarities of Alg. 3 as a kernel of its own (shapes whose key blocks do not line up with the
+// pyramid kernel's workgroups, and callers that already have a pyramid): one workgroup per key block.
+template <typename T>
+__global__ __launch_bounds__(256) void sims_kernel(const T* __restrict__ K, float* __restrict__ sims, int N, int d,
+                                                   int bk, int nk, int H, int chunks) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sim_lds[];
+  const int j = blockIdx.x, bh = blockIdx.y;
+  block_sims<T>(K + (int64_t)bh * N * d, j, N, d, bk, H, chunks, sims + ((int64_t)bh * nk + j) * (H - 1), sim_lds,
+                (int)threadIdx.x, 256);
+}
+
+// L_j = max{1, h : sim_h(j) > tau_s^(h)} (Alg. 3: every level is tested).  all_heads: sim_h(j) is first
+// averaged over batch and heads (the algorithm's one L per block), in a fixed order.
+struct CapArgs {
+  int heads, nk, H, all_heads;
+  float tau[PSA_MAX_LEVELS];
+};
+
+__global__ __launch_bounds__(256) void cap_kernel(const float* __restrict__ sims, uint8_t* __restrict__ L, CapArgs a) {
+  const int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (x >= (int64_t)a.heads * a.nk) return;
+  const int j = (int)(x % a.nk);
+  int lv = 1;
+  for (int h = 2; h <= a.H; ++h) {
+    float sim;
+    if (a.all_heads) {
+      double tot = 0.0;
+      for (int bh = 0; bh < a.heads; ++bh) tot += (double)sims[((int64_t)bh * a.nk + j) * (a.H - 1) + (h - 2)];
+      sim = (float)(tot / (double)a.heads);
+    } else {
+      sim = sims[x * (a.H - 1) + (h - 2)];
+    }
+    if (sim > a.tau[h - 2]) lv = h;
+  }
+  L[x] = (uint8_t)lv;
+}
+
+static size_t sims_lds_bytes(int bk) {
+  return (((size_t)bk * sizeof(float) + 15) & ~(size_t)15) + SIM_MAX_TEAMS * PSA_MAX_LEVELS * sizeof(double);
+}
+
+template <typename T>
+static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, float* sims, hipStream_t s) {
   PyrArgs a;
   a.N = pl.N; a.d = pl.d; a.nk = pl.nk; a.bk = pl.bk;
   a.heads = pl.B * pl.Hkv;
@@ -107,22 +243,52 @@ static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* K
   const T* v = static_cast<const T*>(V);
   T* kp = static_cast<T*>(Kp);
   T* vp = static_cast<T*>(Vp);
+  SimArgs sa;
+  sa.sims = sims; sa.H = pl.H;
+  // the fused form needs the 256 threads of a workgroup to cover whole key blocks
+  const int tpb = a.chunks * (pl.bk >> (pl.H - 1));
+  const bool fused = sims && tpb <= 256 && 256 % tpb == 0;
+  const size_t smem = fused ? sims_lds_bytes(pl.bk) : 0;
+#define PSA_PYR_CASE(HH)                                                                              \
+  case HH:                                                                                            \
+    if (fused) pyramid_kernel<T, HH, true><<<grid, 256, smem, s>>>(k, v, kp, vp, a, sa);              \
+    else pyramid_kernel<T, HH, false><<<grid, 256, 0, s>>>(k, v, kp, vp, a, sa);                      \
+    break;
   switch (pl.H) {
-    case 2: pyramid_kernel<T, 2><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 3: pyramid_kernel<T, 3><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 4: pyramid_kernel<T, 4><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 5: pyramid_kernel<T, 5><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 6: pyramid_kernel<T, 6><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 7: pyramid_kernel<T, 7><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
-    case 8: pyramid_kernel<T, 8><<<grid, 256, 0, s>>>(k, v, kp, vp, a); break;
+    PSA_PYR_CASE(2) PSA_PYR_CASE(3) PSA_PYR_CASE(4) PSA_PYR_CASE(5) PSA_PYR_CASE(6) PSA_PYR_CASE(7) PSA_PYR_CASE(8)
     default: return hipSuccess;  // H == 1: no pooled level
   }
+#undef PSA_PYR_CASE
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !sims || fused) return e;
+  return launch_sims_t<T>(pl, K, sims, s);
+}
+
+template <typename T>
+static hipError_t launch_sims_t(const Plan& pl, const void* K, float* sims, hipStream_t s) {
+  const int chunks = pl.d / Elem<T>::VEC;
+  sims_kernel<T><<<dim3(pl.nk, pl.B * pl.Hkv), 256, sims_lds_bytes(pl.bk), s>>>(
+      static_cast<const T*>(K), sims, pl.N, pl.d, pl.bk, pl.nk, pl.H, chunks);
   return hipGetLastError();
 }
 
-hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, hipStream_t s) {
-  if (pl.dtype == PSA_F32) return launch_t<float>(pl, K, V, Kp, Vp, s);
-  return launch_t<bf16_t>(pl, K, V, Kp, Vp, s);
+hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, float* sims, hipStream_t s) {
+  if (pl.dtype == PSA_F32) return launch_t<float>(pl, K, V, Kp, Vp, sims, s);
+  return launch_t<bf16_t>(pl, K, V, Kp, Vp, sims, s);
+}
+
+hipError_t launch_similarities(const Plan& pl, const void* K, float* sims, hipStream_t s) {
+  if (pl.dtype == PSA_F32) return launch_sims_t<float>(pl, K, sims, s);
+  return launch_sims_t<bf16_t>(pl, K, sims, s);
+}
+
+hipError_t launch_level_cap(const Plan& pl, const float* sims, const float* tau_s, bool all_heads, uint8_t* L, hipStream_t s) {
+  CapArgs a;
+  a.heads = pl.B * pl.Hkv; a.nk = pl.nk; a.H = pl.H; a.all_heads = all_heads ? 1 : 0;
+  for (int h = 0; h < PSA_MAX_LEVELS; ++h) a.tau[h] = h < pl.H - 1 ? tau_s[h] : 0.f;
+  const int64_t n = (int64_t)a.heads * a.nk;
+  cap_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(sims, L, a);
+  return hipGetLastError();
 }
 
 }  // namespace psa
