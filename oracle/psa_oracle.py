@@ -14,7 +14,9 @@ every pooling group vs. dense restricted to the kept blocks (catches a missing/w
 the one-softmax form of Eq. 8 vs. Alg. 1's online recurrence; importance
 with s_q = b_q, s_k = b_k vs. block-max / block-mean of the brute-force attention matrix; Alg. 2 on
 hand-computed rows; Eq. 9 on the printed preset table (Table 9); the similarity cap of Alg. 3 on the
-two identities App. B.1 states (thresholds -1 / 1), a hand-computed planar example and a loop brute force.  No function here is unpinned
+two identities App. B.1 states (thresholds -1 / 1), a hand-computed planar example and a loop brute force;
+the Hilbert reordering on what defines the curve (a bijection whose consecutive cells are face neighbours
+and whose every aligned 8^k run of positions fills an aligned cube of side 2^k).  No function here is unpinned
 against the paper's definitions; end-to-end *quality* on real model activations is unpinned (the
 activations are not available) and only its direction is tested on synthetic data.
 """
@@ -343,6 +345,68 @@ def kv_coverage(M: np.ndarray, p: Params) -> np.ndarray:
     """Fraction of visible KV blocks that are kept (level > 0), per (batch, head)  (App. C.4)."""
     vis = block_visibility(p) > 0
     return ((M > 0) & vis[None, None]).sum(axis=(2, 3)) / float(vis.sum())
+
+
+# --------------------------------------------------------------------------- Sec. 3.3.1: Hilbert reordering
+def hilbert_index_3d(c0: np.ndarray, c1: np.ndarray, c2: np.ndarray, bits: int) -> np.ndarray:
+    """Position along the 3-D Hilbert curve of order `bits` (cube side 2^bits) of the cells with integer
+    coordinates (c0, c1, c2); coordinate 0 supplies the most significant bit of every 3-bit digit.
+
+    The curve is the one produced by Skilling's transpose construction ("Programming the Hilbert curve",
+    2004): undo the per-level reflections/exchanges from the coarsest level down, Gray-encode across
+    the axes, then read the bits of the three words interleaved.
+    """
+    X = [np.asarray(c, dtype=np.int64).copy() for c in (c0, c1, c2)]
+    top = 1 << (bits - 1)
+    q = top
+    while q > 1:                                   # undo excess work, coarsest level first
+        low = q - 1
+        for i in range(3):
+            hit = (X[i] & q) != 0
+            X[0] = np.where(hit, X[0] ^ low, X[0])                         # reflect axis 0
+            t = np.where(hit, 0, (X[0] ^ X[i]) & low)                      # else exchange low bits with axis i
+            X[0] ^= t
+            X[i] ^= t
+        q >>= 1
+    for i in range(1, 3):                          # Gray encode
+        X[i] ^= X[i - 1]
+    t = np.zeros_like(X[0])
+    q = top
+    while q > 1:
+        t = np.where((X[2] & q) != 0, t ^ (q - 1), t)
+        q >>= 1
+    for i in range(3):
+        X[i] ^= t
+    h = np.zeros_like(X[0])
+    for b in range(bits - 1, -1, -1):              # interleave: axis 0 first
+        for i in range(3):
+            h = (h << 1) | ((X[i] >> b) & 1)
+    return h
+
+
+def hilbert_order(T: int, Hg: int, W: int) -> np.ndarray:
+    """Permutation that reorders the tokens of a T x Hg x W grid (raster order, x fastest) along a
+    Hilbert curve (Sec. 3.3.1, video generation; Sec. 4.4 reordering ablation): perm[k] = raster index
+    of the k-th token on the curve; the reordered tensor is X[perm].
+
+    Reading (the paper only names the curve; grids are not powers of two): the curve runs over the
+    enclosing cube of side 2^m, m = ceil(log2 max(T, Hg, W)), coordinates (t, y, x) in that order; cells
+    outside the grid are skipped and the tokens keep the order of their positions on the curve.
+    """
+    side = max(T, Hg, W)
+    bits = max(1, int(math.ceil(math.log2(side)))) if side > 1 else 1
+    t, y, x = np.meshgrid(np.arange(T), np.arange(Hg), np.arange(W), indexing="ij")
+    h = hilbert_index_3d(t.ravel(), y.ravel(), x.ravel(), bits)
+    return np.argsort(h, kind="stable").astype(np.int32)
+
+
+def permute_tokens(X: np.ndarray, perm: np.ndarray, inverse: bool = False) -> np.ndarray:
+    """Reorder the token axis (second to last) of X: forward Y[k] = X[perm[k]]; inverse Y[perm[k]] = X[k]."""
+    if not inverse:
+        return X[..., perm, :]
+    Y = np.empty_like(X)
+    Y[..., perm, :] = X
+    return Y
 
 
 # --------------------------------------------------------------------------- Alg. 3: similarity cap

@@ -529,3 +529,64 @@ def test_similarity_cap_feeds_the_allocation():
     S = orc.importance(Q, K, p)
     M, Mc = orc.allocate_levels(S, p), orc.allocate_levels(S, p, level_cap=L)
     assert np.array_equal(Mc, np.where(M > 0, np.minimum(M, L[:, :1]), 0))
+
+
+# ---------------------------------------------------------------- Sec. 3.3.1: Hilbert reordering
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_hilbert_curve_defining_properties(bits):
+    """On a power-of-two cube the index is a bijection onto 0..8^bits-1, starts at the origin, moves to
+    a face neighbour at every step, and every aligned run of 8^k positions fills an aligned cube of
+    side 2^k (the recursive property that a snake scan, which also moves by face neighbours, lacks)."""
+    n = 1 << bits
+    c = np.stack(np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij"), axis=-1).reshape(-1, 3)
+    h = orc.hilbert_index_3d(c[:, 0], c[:, 1], c[:, 2], bits)
+    assert sorted(h.tolist()) == list(range(n ** 3))
+    path = c[np.argsort(h)]
+    assert tuple(path[0]) == (0, 0, 0)
+    assert np.all(np.abs(np.diff(path, axis=0)).sum(axis=1) == 1)
+    for k in range(1, bits + 1):
+        runs = path.reshape(-1, 8 ** k, 3)
+        lo, hi = runs.min(axis=1), runs.max(axis=1)
+        assert np.all(hi - lo == (1 << k) - 1) and np.all(lo % (1 << k) == 0)
+
+
+@pytest.mark.parametrize("grid", [(4, 16, 16), (21, 30, 52), (3, 5, 7), (1, 1, 9), (1, 6, 4)])
+def test_hilbert_order_is_a_permutation_with_an_inverse(grid):
+    T, Hg, W = grid
+    perm = orc.hilbert_order(T, Hg, W)
+    N = T * Hg * W
+    assert perm.dtype == np.int32 and sorted(perm.tolist()) == list(range(N))
+    X = _rand(70, 2, N, 3)
+    Y = orc.permute_tokens(X, perm)
+    assert np.array_equal(Y[:, 0], X[:, perm[0]]) and np.array_equal(Y[:, N - 1], X[:, perm[N - 1]])
+    assert np.array_equal(orc.permute_tokens(Y, perm, inverse=True), X)
+    # the tokens follow the curve of the enclosing cube: their curve positions increase along the new order
+    side = max(grid)
+    bits = max(1, int(math.ceil(math.log2(side)))) if side > 1 else 1
+    t, y, x = perm // (Hg * W), (perm // W) % Hg, perm % W
+    assert np.all(np.diff(orc.hilbert_index_3d(t, y, x, bits)) > 0)
+
+
+def test_hilbert_order_makes_key_blocks_compact_and_similar():
+    """What the reordering is for (Sec. 3.3.1, Sec. 4.4): a block of consecutive tokens becomes a compact
+    region of the video instead of a strip of a row, so the keys of a block are more alike.  On the
+    synthetic field: the mean spatial extent of a 64-token block shrinks and the mean cosine similarity
+    of keys 8 and 32 positions apart inside a block rises."""
+    import synth_inputs as si
+    w = si.small_variant(si.CONFIGS["dit1p3b"], 32760, Hq=1, Hkv=1)
+    _, K, _ = si.generate_qkv(w)
+    K = si.to_f64(K, w.dtype)
+    T, Hg, W = w.grid
+    perm = orc.hilbert_order(T, Hg, W)
+    p = Params(1, 1, 1, w.N, w.d, 128, 64, 6)
+    before = orc.block_similarities(K, p)[0, 0].mean(axis=0)
+    after = orc.block_similarities(orc.permute_tokens(K, perm), p)[0, 0].mean(axis=0)
+    assert after[2] > before[2] + 0.02 and after[4] > before[4] + 0.1          # strides 8 and 32
+    n = np.arange(w.N)
+    pos = np.stack([n // (Hg * W), (n // W) % Hg, n % W], axis=1)
+
+    def extent(order):
+        blk = pos[order][: (w.N // 64) * 64].reshape(-1, 64, 3)
+        return (blk.max(axis=1) - blk.min(axis=1)).sum(axis=1).mean()
+
+    assert extent(perm) < 0.35 * extent(n)
