@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check-dense", action="store_true", help="skip rel-L2 of PSA vs dense attention")
     ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of sampled query blocks")
+    ap.add_argument("--hilbert", action="store_true",
+                    help="reorder Q, K, V along the Hilbert curve of the workload's token grid before the path and "
+                         "restore the order of O after it (Sec. 3.3.1); the four row permutations are timed as "
+                         "part of the step")
     ap.add_argument("--no-threshold-point", action="store_true",
                     help="skip the second point with Alg. 2's threshold rule (tau = 0.5, 0.7, 0.8, 0.9)")
     return ap.parse_args()
@@ -260,9 +264,25 @@ def main():
     # the two microbenchmarks run first: they also bring the clock to its sustained state
     att = None if args.no_attainable else attainable_peaks(torch, psa)
 
+    hil = None
+    if args.hilbert:
+        T, Hg, W = w.grid
+        if w.text_tokens or T * Hg * W != w.N:
+            print("--hilbert needs a workload whose tokens are exactly its T x Hg x W grid", file=sys.stderr)
+            sys.exit(2)
+        perm_host = psa.psa_hilbert_order(T, Hg, W)
+        hil = {"perm": torch.from_numpy(perm_host).cuda(), "raster": (Qd, Kd, Vd), "O": torch.empty_like(buf.O)}
+        Qd, Kd, Vd = (torch.empty_like(x) for x in hil["raster"])    # the path works on the reordered copies
+
+    def permute_in():
+        for src, dst in zip(hil["raster"], (Qd, Kd, Vd)):
+            psa.psa_permute_tokens(gp, src, hil["perm"], dst)
+
     calls = [lambda: psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr),
              lambda: psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho),
              lambda: psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)]
+    if hil:
+        calls = [permute_in] + calls + [lambda: psa.psa_permute_tokens(gp, buf.O, hil["perm"], hil["O"], inverse=True)]
     for _ in range(args.warmup):
         for fn in calls:
             fn()
@@ -274,6 +294,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     ms_step, mean_ms, median_ms = timed_phases(torch, calls, args.steps)
+    ms_perm = None
+    if hil:
+        ms_perm = mean_ms[0] + mean_ms[-1]
+        mean_ms, median_ms = mean_ms[1:-1], median_ms[1:-1]
     ms_pyr, ms_alloc, ms_attn = mean_ms
 
     M = buf.M.cpu().numpy()
@@ -315,6 +339,14 @@ def main():
             "note": "K, V read + pooled levels written + Q read + level-H keys read + S written and read + M written, "
                     "over the mean HIP-event time of the two calls"},
     }
+    if hil:
+        e = 2 if w.dtype == "bf16" else 4
+        perm_bytes = 2.0 * e * w.N * w.d * w.B * (2 * w.Hq + 2 * w.Hkv)     # Q, K, V in and O out, each read and written once
+        out["config"]["reorder"] = "hilbert"
+        out["phases_ms"]["permute_qkv_and_o"] = ms_perm
+        out["roofline_permute"] = {"kernel": "permute_kernel (4 launches)", "bound": "hbm", "achieved": perm_bytes / (ms_perm * 1e-3) / 1e9,
+                                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": perm_bytes / (ms_perm * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                   "algorithmic_bytes": perm_bytes}
     if att is not None:
         out["attainable"] = att
         out["roofline"]["frac_of_attainable"] = attn_tflops / att["mfma_bf16_tflops"]
@@ -325,6 +357,9 @@ def main():
     if w.dtype != "bf16":
         out["roofline"]["note"] += "; fp32 mode runs on the VALU (correctness mode), bf16 MFMA peak shown for scale only"
     if not args.no_parity:
+        if hil:      # the path saw the reordered tensors: give the oracle the same
+            from oracle import psa_oracle as orc
+            Q, K, V = (orc.permute_tokens(x, perm_host) for x in (Q, K, V))
         out.update(parity_leg(w, gp, budget, Q, K, V, buf, torch))
     if not args.no_check_dense:
         # dense attention = the same call with every block at level 1 (that equality is a parity test)

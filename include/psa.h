@@ -4,6 +4,7 @@
  * The four calls are the stages of the method in "PSA: Pyramid Sparse Attention":
  *   psa_build_pyramid    Sec. 3.2, Eq. 2-3   mean-pooled K/V pyramid
  *   psa_level_cap        App. B.1, Alg. 3    optional cosine-similarity cap on the level of a key block
+ *   psa_hilbert_order, psa_permute_tokens   Sec. 3.3.1 / 4.4   optional Hilbert-curve token reordering
  *   psa_allocate_levels  Sec. 3.3, Eq. 4, Alg. 2, Eq. 5-7 (+ the quantile rule of Sec. 4.4)
  *   psa_attention_fwd    Sec. 3.4, Alg. 1, Eq. 8   online-softmax attention over mixed-level KV blocks
  *   psa_dense_ref        Sec. 3.1, Eq. 1     plain softmax attention (reference / comparison)
@@ -84,6 +85,28 @@ int psa_query_sizes(const psa_params* p, size_t* pyr_bytes, size_t* scratch_byte
  */
 int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* Kpyr, void* Vpyr,
                       void* stream);
+
+/*
+ * Hilbert-curve reordering of the tokens of a video latent grid, Sec. 3.3.1 (video-generation estimator)
+ * and the reordering ablation of Sec. 4.4: Q, K and V are permuted before the path so that a block of
+ * consecutive tokens is a compact region of the video, and O is permuted back.
+ *
+ * psa_hilbert_order (host call, no GPU work): perm[k] = raster index (x fastest, then y, then t) of the
+ *   k-th token along the 3-D Hilbert curve over the cube of side 2^m enclosing the T x Hg x W grid,
+ *   m = ceil(log2 max(T, Hg, W)), coordinates (t, y, x); cells outside the grid are skipped.
+ *   perm: HOST, out, int32 [T * Hg * W].  The order depends on the grid only: build it once.
+ *   Errors: PSA_EINVAL (non-positive size, null), PSA_EUNSUPPORTED (more than 2^31-1 tokens).
+ * psa_permute_tokens: one tensor X [heads, N, d] of p->dtype (heads = B * Hq for Q and O, B * Hkv for K
+ *   and V; p supplies N, d, dtype) -> Y of the same shape.
+ *     inverse = 0:  Y[h, k, :] = X[h, perm[k], :]      (apply to Q, K, V)
+ *     inverse != 0: Y[h, perm[k], :] = X[h, k, :]      (apply to O)
+ *   perm: DEVICE, int32 [N], a permutation of 0..N-1; a row whose entry is out of range is skipped.
+ *   X and Y must not overlap.  Asynchronous on `stream`.
+ *   Errors: PSA_EINVAL (null pointer, X == Y, heads outside 1..65535), PSA_ELAUNCH.
+ */
+int psa_hilbert_order(int32_t T, int32_t Hg, int32_t W, int32_t* perm);
+int psa_permute_tokens(const psa_params* p, int32_t heads, const void* X, const int32_t* perm,
+                       int32_t inverse, void* Y, void* stream);
 
 /*
  * Cosine-similarity pooling constraint, App. B.1 / Alg. 3: the maximum admissible level of every key

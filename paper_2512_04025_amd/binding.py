@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.psa_query_sizes.argtypes = [pp, szp, szp]
     lib.psa_build_pyramid.argtypes = [pp, vp, vp, vp, vp, vp]
     fp = ctypes.POINTER(ctypes.c_float)
+    lib.psa_hilbert_order.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    lib.psa_permute_tokens.argtypes = [pp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp]
     lib.psa_level_cap.argtypes = [pp, vp, fp, ctypes.c_int, vp, vp, vp]
     lib.psa_build_pyramid_cap.argtypes = [pp, vp, vp, vp, vp, fp, ctypes.c_int, vp, vp, vp]
     lib.psa_allocate_levels.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -74,7 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
     for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_attention_fwd_static",
-                 "psa_level_cap", "psa_build_pyramid_cap",
+                 "psa_level_cap", "psa_build_pyramid_cap", "psa_hilbert_order", "psa_permute_tokens",
                  "psa_dense_ref", "psa_probe_copy", "psa_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -131,6 +133,23 @@ def psa_query_sizes(p: PsaParams) -> Tuple[int, int]:
 def psa_build_pyramid(p: PsaParams, K, V, Kpyr, Vpyr, stream=None) -> None:
     _check(load_library().psa_build_pyramid(ctypes.byref(p), _ptr(K), _ptr(V), _ptr(Kpyr), _ptr(Vpyr),
                                             _stream(stream)), "psa_build_pyramid")
+
+
+def psa_hilbert_order(T: int, Hg: int, W: int):
+    """Host call: the Hilbert-curve token order of a T x Hg x W grid as a numpy int32 array."""
+    import numpy as np
+    perm = np.empty(T * Hg * W, dtype=np.int32)
+    _check(load_library().psa_hilbert_order(T, Hg, W, perm.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))),
+           "psa_hilbert_order")
+    return perm
+
+
+def psa_permute_tokens(p: PsaParams, X, perm, Y, inverse: bool = False, stream=None) -> None:
+    """X, Y: [..., N, d] device tensors of p's dtype (all leading axes are heads); perm: device int32 [N]."""
+    heads = X.numel() // (p.N * p.d)
+    _check(load_library().psa_permute_tokens(ctypes.byref(p), ctypes.c_int32(heads), _ptr(X), _ptr(perm),
+                                             ctypes.c_int32(1 if inverse else 0), _ptr(Y), _stream(stream)),
+           "psa_permute_tokens")
 
 
 def _thresholds(p: PsaParams, tau_s: Sequence[float]):

@@ -159,6 +159,22 @@ int psa_build_pyramid(const psa_params* p, const void* K, const void* V, void* K
   return launch_pyramid(pl, K, V, Kpyr, Vpyr, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 
+int psa_hilbert_order(int32_t T, int32_t Hg, int32_t W, int32_t* perm) {
+  if (T <= 0 || Hg <= 0 || W <= 0 || !perm) return PSA_EINVAL;
+  if ((int64_t)T * Hg * W > 0x7fffffff) return PSA_EUNSUPPORTED;
+  if (T > (1 << 20) || Hg > (1 << 20) || W > (1 << 20)) return PSA_EUNSUPPORTED;   // 3 x 21 bits of curve position
+  return hilbert_order_host(T, Hg, W, perm);
+}
+
+int psa_permute_tokens(const psa_params* p, int32_t heads, const void* X, const int32_t* perm, int32_t inverse,
+                       void* Y, void* stream) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  if (heads <= 0 || heads > 65535 || !X || !perm || !Y || X == Y) return PSA_EINVAL;
+  return launch_permute(pl, heads, X, perm, inverse != 0, Y, static_cast<hipStream_t>(stream)) == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
 static int check_cap_args(const Plan& pl, const float* tau_s, int reduce, const float* sim, const uint8_t* L) {
   if (!L || (reduce != PSA_CAP_PER_HEAD && reduce != PSA_CAP_ALL_HEADS)) return PSA_EINVAL;
   if (pl.H > 1 && (!tau_s || !sim)) return PSA_EINVAL;

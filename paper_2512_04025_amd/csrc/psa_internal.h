@@ -57,6 +57,9 @@ hipError_t launch_pyramid(const Plan& pl, const void* K, const void* V, void* Kp
 hipError_t launch_similarities(const Plan& pl, const void* K, float* sims, hipStream_t s);
 // tau_s: host, H-1 thresholds for levels 2..H; L: uint8 [B*Hkv][nk]
 hipError_t launch_level_cap(const Plan& pl, const float* sims, const float* tau_s, bool all_heads, uint8_t* L, hipStream_t s);
+// Hilbert-curve token order of a T x Hg x W grid (host) and the row gather / scatter that applies it
+int hilbert_order_host(int T, int Hg, int W, int32_t* perm);
+hipError_t launch_permute(const Plan& pl, int heads, const void* X, const int32_t* perm, bool inverse, void* Y, hipStream_t s);
 hipError_t launch_representatives(const Plan& pl, const void* X, void* R, bool is_query, hipStream_t s);
 // part: per (row, key slice) partial softmax statistics of the matrix-core path (Plan::off_part)
 // bmax: per (representative row, key block) largest logit, kept for max pooling (Plan::off_bmax)

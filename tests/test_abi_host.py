@@ -93,3 +93,19 @@ def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libpsa.so"))
     with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
         binding.load_library()
+
+
+@pytest.mark.parametrize("grid", [(4, 16, 16), (21, 30, 52), (3, 5, 7), (1, 1, 9), (2, 2, 2), (1, 1, 1), (5, 64, 33)])
+def test_hilbert_order_matches_the_oracle(lib, grid):
+    """The library's host-side Hilbert order (its own C++ statement of the curve) against the oracle's."""
+    import numpy as np
+    from oracle import psa_oracle as orc
+    got = psa.psa_hilbert_order(*grid)
+    assert got.dtype == np.int32 and np.array_equal(got, orc.hilbert_order(*grid))
+
+
+def test_hilbert_order_rejects_bad_grids(lib):
+    one = (ctypes.c_int32 * 1)()
+    assert lib.psa_hilbert_order(0, 4, 4, one) == 1
+    assert lib.psa_hilbert_order(4, 4, 4, None) == 1
+    assert lib.psa_hilbert_order(1 << 11, 1 << 11, 1 << 11, one) == 2
