@@ -15,7 +15,8 @@ the one-softmax form of Eq. 8 vs. Alg. 1's online recurrence; importance
 with s_q = b_q, s_k = b_k vs. block-max / block-mean of the brute-force attention matrix; Alg. 2 on
 hand-computed rows; Eq. 9 on the printed preset table (Table 9); the similarity cap of Alg. 3 on the
 two identities App. B.1 states (thresholds -1 / 1), a hand-computed planar example and a loop brute force;
-the Hilbert reordering on what defines the curve (a bijection whose consecutive cells are face neighbours
+the backward pass on automatic differentiation of an independent plain-PyTorch statement of Eq. 8 and on
+finite differences; the Hilbert reordering on what defines the curve (a bijection whose consecutive cells are face neighbours
 and whose every aligned 8^k run of positions fills an aligned cube of side 2^k).  No function here is unpinned
 against the paper's definitions; end-to-end *quality* on real model activations is unpinned (the
 activations are not available) and only its direction is tested on synthetic data.
@@ -86,7 +87,10 @@ def _round_bf16(x32: np.ndarray) -> np.ndarray:
 
 
 def round_store(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Round fp64 values to the storage type (via fp32) and return them as fp64."""
+    """Round fp64 values to the storage type (via fp32) and return them as fp64 ("f64": no rounding,
+    for checks that need the pooling to be exactly linear)."""
+    if dtype == "f64":
+        return np.asarray(x, dtype=np.float64)
     x32 = np.asarray(x, dtype=np.float64).astype(np.float32)
     if dtype == "bf16":
         x32 = _round_bf16(x32)
@@ -549,6 +553,69 @@ def psa_attention_online(Q, Kp, Vp, M, p: Params, b: int, hq: int, i: int) -> np
         o = alpha[:, None] * o + P @ Vp[h][b, hk][idx]
         m = m_new
     return o / l[:, None]
+
+
+# --------------------------------------------------------------------------- backward of Alg. 1 / Eq. 8
+def psa_attention_backward(Q: np.ndarray, Kp: Dict[int, np.ndarray], Vp: Dict[int, np.ndarray], M: np.ndarray,
+                           dO: np.ndarray, p: Params):
+    """Gradients of the adaptive pyramid attention (Eq. 8) with respect to Q, K and V, given dO.
+
+    The paper states that its kernel supports backpropagation (Sec. 1) and prints no formulas; these
+    follow from Eq. 8 and Eq. 2-3 by the chain rule.  For one query row with kept pooled keys g, logits
+    s_g = scale q.kbar_g + ln c_g, weights P_g = softmax(s)_g and output o = sum_g P_g vbar_g:
+        dP_g = dO . vbar_g,   D = sum_g P_g dP_g (= dO . o),   dS_g = P_g (dP_g - D),
+        dq = scale sum_g dS_g kbar_g,   dkbar_g += scale dS_g q,   dvbar_g += P_g dO,
+    and a pooled token is the mean of the c_g tokens under it (Eq. 2-3), so every one of them receives
+    dkbar_g / c_g and dvbar_g / c_g.  Readings: the level map M is a constant (the allocation is a
+    discrete decision: no gradient flows through the scores); the bias ln c_g is a constant; the
+    rounding of the stored pyramid is treated as the identity.  Query heads that share a key head add up.
+    Returns (dQ [B,Hq,N,d], dK [B,Hkv,N,d], dV [B,Hkv,N,d]) in fp64.
+    """
+    group = p.Hq // p.Hkv
+    dQ = np.zeros((p.B, p.Hq, p.N, p.d))
+    dKp = {h: np.zeros_like(Kp[h]) for h in range(1, p.levels + 1)}
+    dVp = {h: np.zeros_like(Vp[h]) for h in range(1, p.levels + 1)}
+    for b in range(p.B):
+        for hq in range(p.Hq):
+            hk = hq // group
+            for i in range(p.nq):
+                rows = np.arange(i * p.bq, min((i + 1) * p.bq, p.N))
+                Qi, dOi = Q[b, hq, rows], dO[b, hq, rows]
+                logits, where = [], []
+                for j in range(p.nk):
+                    h = int(M[b, hq, i, j])
+                    if h:
+                        s, idx = _block_logits(Qi, rows, Kp[h][b, hk], j, h, p)
+                        logits.append(s)
+                        where.append((h, idx))
+                if not logits:
+                    continue
+                s = np.concatenate(logits, axis=1)
+                mx = s.max(axis=1, keepdims=True)
+                w = np.exp(s - np.where(np.isfinite(mx), mx, 0.0))
+                P = w / w.sum(axis=1, keepdims=True)
+                kbar = np.concatenate([Kp[h][b, hk][idx] for h, idx in where], axis=0)
+                vbar = np.concatenate([Vp[h][b, hk][idx] for h, idx in where], axis=0)
+                dP = dOi @ vbar.T
+                D = (P * dP).sum(axis=1, keepdims=True)
+                dS = P * (dP - D)
+                dQ[b, hq, rows] = p.sm_scale * (dS @ kbar)
+                dkb = p.sm_scale * (dS.T @ Qi)
+                dvb = P.T @ dOi
+                c0 = 0
+                for h, idx in where:
+                    dKp[h][b, hk][idx] += dkb[c0:c0 + idx.size]
+                    dVp[h][b, hk][idx] += dvb[c0:c0 + idx.size]
+                    c0 += idx.size
+    # back through the mean pooling of Eq. 2-3: a pooled token's gradient is shared by the tokens under it
+    dK = dKp[1][:, :, :p.N].copy()
+    dV = dVp[1][:, :, :p.N].copy()
+    for h in range(2, p.levels + 1):
+        g = 1 << (h - 1)
+        cnt = np.maximum(pooled_counts(p, h), 1).astype(np.float64)
+        dK += np.repeat(dKp[h] / cnt[None, None, :, None], g, axis=2)[:, :, :p.N]
+        dV += np.repeat(dVp[h] / cnt[None, None, :, None], g, axis=2)[:, :, :p.N]
+    return dQ, dK, dV
 
 
 # --------------------------------------------------------------------------- Eq. 1: dense attention

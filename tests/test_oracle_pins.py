@@ -590,3 +590,95 @@ def test_hilbert_order_makes_key_blocks_compact_and_similar():
         return (blk.max(axis=1) - blk.min(axis=1)).sum(axis=1).mean()
 
     assert extent(perm) < 0.35 * extent(n)
+
+
+# ---------------------------------------------------------------- backward of Alg. 1 / Eq. 8
+def _torch_psa_forward(Q, K, V, M, p):
+    """Eq. 8 in plain PyTorch (fp64, differentiable), written independently of the oracle: per query row
+    a python-level gather of the kept pooled tokens, pooled by explicit means of the tokens under them."""
+    import torch
+    group = p.Hq // p.Hkv
+    out = torch.zeros_like(Q)
+    for b in range(p.B):
+        for hq in range(p.Hq):
+            hk = hq // group
+            for i in range(p.nq):
+                r0, r1 = i * p.bq, min((i + 1) * p.bq, p.N)
+                for r in range(r0, r1):
+                    ks, vs, bias = [], [], []
+                    for j in range(p.nk):
+                        h = int(M[b, hq, i, j])
+                        if h == 0:
+                            continue
+                        g = 1 << (h - 1)
+                        for t0 in range(j * p.bk, min((j + 1) * p.bk, p.N), g):
+                            t1 = min(t0 + g, p.N)
+                            if p.causal and t1 - 1 > r:
+                                continue
+                            ks.append(K[b, hk, t0:t1].mean(dim=0))
+                            vs.append(V[b, hk, t0:t1].mean(dim=0))
+                            bias.append(math.log(t1 - t0))
+                    kk, vv = torch.stack(ks), torch.stack(vs)
+                    s = (kk @ Q[b, hq, r]) * p.sm_scale + torch.tensor(bias, dtype=torch.float64)
+                    out[b, hq, r] = torch.softmax(s, dim=0) @ vv
+    return out
+
+
+@pytest.mark.parametrize("N,causal,H", [(48, False, 3), (43, False, 3), (45, True, 2)])
+def test_backward_matches_autograd_of_an_independent_forward(N, causal, H):
+    import torch
+    p = Params(1, 2, 1, N, 4, 8, 8, H, dtype="f64", causal=causal)
+    rng = np.random.default_rng(80 + N)
+    Q, K, V, dO = (rng.standard_normal(sh) for sh in [(1, 2, N, 4), (1, 1, N, 4), (1, 1, N, 4), (1, 2, N, 4)])
+    M = rng.integers(0, H + 1, size=(1, 2, p.nq, p.nk)).astype(np.uint8)
+    vis = orc.block_visibility(p)
+    M = np.where(vis[None, None] == 0, 0, M)
+    M = np.where(vis[None, None] == 2, 1, M).astype(np.uint8)
+    M[..., 0] = 1
+    Kp, Vp = orc.build_pyramid(K, p), orc.build_pyramid(V, p)
+    O, _ = orc.psa_attention(Q, Kp, Vp, M, p)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    tO = _torch_psa_forward(tq, tk, tv, M, p)
+    np.testing.assert_allclose(tO.detach().numpy(), O, rtol=1e-10, atol=1e-12)       # same forward
+    tO.backward(torch.tensor(dO))
+    dQ, dK, dV = orc.psa_attention_backward(Q, Kp, Vp, M, dO, p)
+    np.testing.assert_allclose(dQ, tq.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dK, tk.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dV, tv.grad.numpy(), rtol=1e-9, atol=1e-11)
+
+
+def test_backward_matches_finite_differences():
+    p = Params(1, 1, 1, 40, 3, 8, 8, 3, dtype="f64")
+    rng = np.random.default_rng(90)
+    Q, K, V, W = (rng.standard_normal((1, 1, 40, 3)) for _ in range(4))
+    M = rng.integers(0, 4, size=(1, 1, p.nq, p.nk)).astype(np.uint8)
+    M[..., 0] = 2
+
+    def loss(q, k, v):
+        O, _ = orc.psa_attention(q, orc.build_pyramid(k, p), orc.build_pyramid(v, p), M, p)
+        return float((O * W).sum())
+
+    dQ, dK, dV = orc.psa_attention_backward(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, W, p)
+    eps = 1e-6
+    for which, grad in enumerate((dQ, dK, dV)):
+        for _ in range(6):
+            n, c = int(rng.integers(0, 40)), int(rng.integers(0, 3))
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[which][0, 0, n, c] += eps
+            up = loss(*args)
+            args[which][0, 0, n, c] -= 2 * eps
+            fd = (up - loss(*args)) / (2 * eps)
+            assert abs(fd - grad[0, 0, n, c]) <= 1e-7 * max(1.0, abs(fd))
+
+
+def test_backward_all_level1_is_dense_attention_backward():
+    import torch
+    p = Params(1, 2, 2, 24, 4, 8, 8, 3, dtype="f64")
+    rng = np.random.default_rng(91)
+    Q, K, V, dO = (rng.standard_normal((1, 2, 24, 4)) for _ in range(4))
+    M = np.ones((1, 2, p.nq, p.nk), dtype=np.uint8)
+    tq, tk, tv = (torch.tensor(x, requires_grad=True) for x in (Q, K, V))
+    (torch.softmax(tq @ tk.transpose(-1, -2) * p.sm_scale, dim=-1) @ tv).backward(torch.tensor(dO))
+    dQ, dK, dV = orc.psa_attention_backward(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, dO, p)
+    for got, want in ((dQ, tq.grad), (dK, tk.grad), (dV, tv.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-10, atol=1e-12)
