@@ -7,6 +7,7 @@
  *   psa_hilbert_order, psa_permute_tokens   Sec. 3.3.1 / 4.4   optional Hilbert-curve token reordering
  *   psa_allocate_levels  Sec. 3.3, Eq. 4, Alg. 2, Eq. 5-7 (+ the quantile rule of Sec. 4.4)
  *   psa_attention_fwd    Sec. 3.4, Alg. 1, Eq. 8   online-softmax attention over mixed-level KV blocks
+ *   psa_attention_bwd    Sec. 1 (claim), derived from Eq. 8 and Eq. 2-3   gradients of the above
  *   psa_dense_ref        Sec. 3.1, Eq. 1     plain softmax attention (reference / comparison)
  *
  * Conventions for every call
@@ -184,6 +185,28 @@ int psa_allocate_levels(const psa_params* p, const void* Q, const void* K, const
 int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const void* V,
                       const void* Kpyr, const void* Vpyr, const uint8_t* M, void* O, float* lse,
                       void* scratch, void* stream);
+
+/*
+ * Backward pass of psa_attention_fwd (the paper's kernel "supports backpropagation", Sec. 1; it prints
+ * no formulas: these are the chain rule through Eq. 8 and the mean pooling of Eq. 2-3).  With
+ * P = exp(s - lse) for every kept pooled key of a query row, dP = dO . vbar, D = dO . O, dS = P (dP - D):
+ *   dQ = scale * sum dS kbar;  the pooled key and value receive scale * sum_rows dS q and sum_rows P dO,
+ *   and each of the c tokens under a pooled token receives 1/c of its gradient.
+ * The level map M is a constant (no gradient flows through the allocation); query heads that share a
+ * key head add up in dK, dV.
+ *   Q, K, V, Kpyr, Vpyr, M   as given to psa_attention_fwd
+ *   O, lse      its outputs (lse is required here: float [B, Hq, N])
+ *   dO          [B, Hq, N, d], dtype
+ *   dQ          out [B, Hq, N, d];  dK, dV  out [B, Hkv, N, d], dtype (every element is written)
+ *   scratch     workspace of psa_query_bwd_sizes' scratch_bytes (256-byte aligned): D, block lists, and the
+ *               fp32 gradients of the pooled tokens of every level
+ * All arithmetic is fp32 on the vector unit for both element types, without atomics (bit-reproducible).
+ * Errors: PSA_EINVAL (null pointer, misaligned scratch), PSA_EUNSUPPORTED (b_k > 128), PSA_ELAUNCH.
+ */
+int psa_query_bwd_sizes(const psa_params* p, size_t* scratch_bytes);
+int psa_attention_bwd(const psa_params* p, const void* Q, const void* K, const void* V, const void* Kpyr,
+                      const void* Vpyr, const uint8_t* M, const void* O, const float* lse, const void* dO,
+                      void* dQ, void* dK, void* dV, void* scratch, void* stream);
 
 /*
  * psa_attention_fwd for callers that cannot hand over a workspace or allocate one: code recorded into

@@ -70,13 +70,15 @@ def load_library() -> ctypes.CDLL:
     lib.psa_allocate_levels.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psa_attention_fwd_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.psa_query_bwd_sizes.argtypes = [pp, szp]
+    lib.psa_attention_bwd.argtypes = [pp] + [vp] * 14
     lib.psa_dense_ref.argtypes = [pp, vp, vp, vp, vp, vp, vp]
     lib.psa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.psa_probe_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), vp]
     lib.psa_status_str.argtypes = [ctypes.c_int]
     lib.psa_status_str.restype = ctypes.c_char_p
     for name in ("psa_query_sizes", "psa_build_pyramid", "psa_allocate_levels", "psa_attention_fwd", "psa_attention_fwd_static",
-                 "psa_level_cap", "psa_build_pyramid_cap", "psa_hilbert_order", "psa_permute_tokens",
+                 "psa_level_cap", "psa_build_pyramid_cap", "psa_query_bwd_sizes", "psa_attention_bwd", "psa_hilbert_order", "psa_permute_tokens",
                  "psa_dense_ref", "psa_probe_copy", "psa_probe_mfma"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -188,6 +190,18 @@ def psa_attention_fwd_static(p: PsaParams, Q, K, V, Kpyr, Vpyr, M, O, lse=None, 
     _check(load_library().psa_attention_fwd_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(Kpyr),
                                                    _ptr(Vpyr), _ptr(M), _ptr(O), _ptr(lse), _stream(stream)),
            "psa_attention_fwd_static")
+
+
+def psa_query_bwd_sizes(p: PsaParams) -> int:
+    scr = ctypes.c_size_t(0)
+    _check(load_library().psa_query_bwd_sizes(ctypes.byref(p), ctypes.byref(scr)), "psa_query_bwd_sizes")
+    return scr.value
+
+
+def psa_attention_bwd(p: PsaParams, Q, K, V, Kpyr, Vpyr, M, O, lse, dO, dQ, dK, dV, scratch, stream=None) -> None:
+    _check(load_library().psa_attention_bwd(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(Kpyr), _ptr(Vpyr),
+                                            _ptr(M), _ptr(O), _ptr(lse), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                            _ptr(scratch), _stream(stream)), "psa_attention_bwd")
 
 
 def psa_dense_ref(p: PsaParams, Q, K, V, O, lse=None, stream=None) -> None:

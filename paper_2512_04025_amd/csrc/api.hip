@@ -296,6 +296,53 @@ int psa_dense_ref(const psa_params* p, const void* Q, const void* K, const void*
   return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 
+// ---- backward pass
+struct BwdLayout { size_t off_D, off_idx, off_cnt, off_dkp, off_dvp, bytes; };
+
+static BwdLayout bwd_layout(const Plan& pl) {
+  BwdLayout l;
+  const size_t rows_q = (size_t)pl.B * pl.Hq * pl.nq;
+  size_t s = 0;
+  l.off_D = s;   s += align256((size_t)pl.B * pl.Hq * pl.N * sizeof(float));
+  l.off_idx = s; s += align256(rows_q * pl.nk * sizeof(uint16_t));
+  l.off_cnt = s; s += align256(rows_q * CNT_STRIDE * sizeof(int32_t));
+  l.off_dkp = s; s += align256(bwd_pooled_grad_elems(pl) * sizeof(float));
+  l.off_dvp = s; s += align256(bwd_pooled_grad_elems(pl) * sizeof(float));
+  l.bytes = s;
+  return l;
+}
+
+int psa_query_bwd_sizes(const psa_params* p, size_t* scratch_bytes) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  if (pl.bk > 128) return PSA_EUNSUPPORTED;
+  if (scratch_bytes) *scratch_bytes = bwd_layout(pl).bytes;
+  return PSA_OK;
+}
+
+int psa_attention_bwd(const psa_params* p, const void* Q, const void* K, const void* V, const void* Kpyr,
+                      const void* Vpyr, const uint8_t* M, const void* O, const float* lse, const void* dO, void* dQ,
+                      void* dK, void* dV, void* scratch, void* stream) {
+  Plan pl;
+  const int rc = make_plan(p, &pl);
+  if (rc != PSA_OK) return rc;
+  if (!Q || !K || !V || !M || !O || !lse || !dO || !dQ || !dK || !dV || !scratch) return PSA_EINVAL;
+  if (pl.H > 1 && (!Kpyr || !Vpyr)) return PSA_EINVAL;
+  if (reinterpret_cast<uintptr_t>(scratch) & 255) return PSA_EINVAL;
+  if (pl.bk > 128) return PSA_EUNSUPPORTED;      // four lanes per pooled key of a block in one workgroup
+  const BwdLayout l = bwd_layout(pl);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint16_t* idx = reinterpret_cast<uint16_t*>(at(scratch, l.off_idx));
+  int32_t* cnt = reinterpret_cast<int32_t*>(at(scratch, l.off_cnt));
+  if (launch_schedule(pl, M, idx, cnt, s) != hipSuccess) return PSA_ELAUNCH;
+  const hipError_t e = launch_attn_bwd(pl, Q, K, V, Kpyr, Vpyr, M, idx, cnt, O, lse, dO,
+                                       reinterpret_cast<float*>(at(scratch, l.off_D)),
+                                       reinterpret_cast<float*>(at(scratch, l.off_dkp)),
+                                       reinterpret_cast<float*>(at(scratch, l.off_dvp)), dQ, dK, dV, s);
+  return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
+}
+
 // ---- psa_attention_fwd_static: the same kernels, their workspace in a static device array.
 // In host code the array's name is only a handle for hipGetSymbolAddress: the address the kernels get
 // is looked up once per device (each GPU holds its own copy) and kept in static_ptr.

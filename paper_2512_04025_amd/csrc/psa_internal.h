@@ -86,4 +86,11 @@ hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const 
                             const void* Vp, const uint16_t* idx, const int32_t* cnt, const uint32_t* desc, void* O,
                             float* lse, hipStream_t s);
 
+// Backward of the pyramid attention.  Dr: [B*Hq*N] floats; dKp, dVp: pooled gradients of levels 1..H
+// (bwd_pooled_grad_elems floats each); idx / cnt: the level-sorted block lists of launch_schedule.
+size_t bwd_pooled_grad_elems(const Plan& pl);
+hipError_t launch_attn_bwd(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
+                           const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const void* O, const float* lse,
+                           const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, hipStream_t s);
+
 }  // namespace psa

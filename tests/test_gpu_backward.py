@@ -1,0 +1,107 @@
+"""GPU parity of the backward pass of the pyramid attention against the oracle (chain rule through
+Eq. 8 and the mean pooling of Eq. 2-3).
+
+Tolerances.  fp32 mode: every step is fp32 with accurate exp, sums of at most a few thousand terms:
+1e-5 of the largest gradient entry, rel-L2 1e-5.  bf16: inputs and the forward's O are bf16, arithmetic is
+fp32 and the gradients are rounded to bf16 once (relative 2^-9): the forward's bar, max-abs 2e-2 of the
+largest entry and rel-L2 1e-2."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import psa_oracle as orc
+from tests.psa_testlib import Buffers, from_dev, gpu_params, oracle_params, rel_l2, to_dev
+from tests.test_gpu_parity import _case
+
+pytestmark = pytest.mark.gpu
+
+psa = pytest.importorskip("paper_2512_04025_amd")
+
+
+def _backward_case(name, over, mask=None, seed=0):
+    import torch
+    w, _ = _case(name)
+    op = oracle_params(w, **over)
+    gp = gpu_params(op)
+    Q, K, V = si.generate_qkv(w)
+    rng = np.random.default_rng(1000 + seed)
+    dO32 = rng.standard_normal((op.B, op.Hq, op.N, op.d)).astype(np.float32)
+    dO = si.f32_to_bf16_bits(dO32) if w.dtype == "bf16" else dO32
+    Q64, K64, V64, dO64 = (si.to_f64(x, w.dtype) for x in (Q, K, V, dO))
+    Qd, Kd, Vd, dOd = (to_dev(x, w.dtype) for x in (Q, K, V, dO))
+    buf = Buffers(gp)
+    Kp, Vp = orc.build_pyramid(K64, op), orc.build_pyramid(V64, op)
+    if mask is None:
+        mask = orc.allocate_levels(orc.importance(Q64, K64, op), op)
+    Md = torch.from_numpy(mask).cuda()
+    psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+    psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, Md, buf.O, buf.scratch, lse=buf.lse)
+    scratch = torch.empty(psa.psa_query_bwd_sizes(gp), dtype=torch.uint8, device="cuda")
+    dQ, dK, dV = (torch.full_like(x, float("nan")) for x in (Qd, Kd, Vd))
+    psa.psa_attention_bwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, Md, buf.O, buf.lse, dOd, dQ, dK, dV, scratch)
+    torch.cuda.synchronize()
+    ref = orc.psa_attention_backward(Q64, Kp, Vp, mask, dO64, op)
+    tol_abs, tol_l2 = (1e-5, 1e-5) if w.dtype == "f32" else (2e-2, 1e-2)
+    for nm, got_d, want in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        got = from_dev(got_d, w.dtype)
+        assert np.all(np.isfinite(got)), nm
+        scale = max(float(np.abs(want).max()), 1e-30)
+        assert np.abs(got - want).max() <= tol_abs * max(scale, 1.0), (nm, np.abs(got - want).max(), scale)
+        assert rel_l2(got, want) <= tol_l2, (nm, rel_l2(got, want))
+    return op
+
+
+@pytest.mark.parametrize("name,over", [
+    ("tiny", {}),
+    ("tiny", dict(alloc_mode="threshold", tau=(0.7, 0.8, 0.9, 0.9))),
+    ("f32_d128", dict(budget=0.3)),
+    ("dit_small", dict(budget=0.2)),
+    ("dit_odd", dict(budget=0.3)),
+    ("vlm_small", dict(budget=0.25)),
+    ("vlm_ragged", dict(budget=0.4)),
+    ("stress_small", dict(budget=0.2)),
+    ("b32", dict(budget=0.3)),
+    ("deep_d64", dict(budget=0.2)),
+    ("edge_one_partial_block", dict(budget=0.5)),
+    ("edge_single_level", dict(budget=0.5)),
+    ("edge_eight_levels", dict(budget=0.5)),
+])
+def test_backward_matches_oracle(name, over):
+    _backward_case(name, over)
+
+
+@pytest.mark.parametrize("name", ["dit_odd", "vlm_ragged", "tiny"])
+def test_backward_random_masks(name):
+    w, _ = _case(name)
+    op = oracle_params(w)
+    rng = np.random.default_rng(21)
+    vis = orc.block_visibility(op)
+    M = rng.integers(0, op.levels + 1, size=(op.B, op.Hq, op.nq, op.nk)).astype(np.uint8)
+    M[:, :, 1::3] = np.where(M[:, :, 1::3] > 0, op.levels, 0)
+    M[..., 0] = 1
+    M = np.where(vis[None, None] == 0, 0, M)
+    M = np.where(vis[None, None] == 2, 1, M).astype(np.uint8)
+    _backward_case(name, {}, mask=M, seed=1)
+
+
+def test_backward_is_reproducible_bit_for_bit():
+    import torch
+    w, _ = _case("dit_small")
+    gp = gpu_params(oracle_params(w))
+    Q, K, V = si.generate_qkv(w)
+    Qd, Kd, Vd = (to_dev(x, w.dtype) for x in (Q, K, V))
+    buf = Buffers(gp)
+    psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+    psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch)
+    psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch, lse=buf.lse)
+    dO = torch.randn_like(buf.O)
+    scratch = torch.empty(psa.psa_query_bwd_sizes(gp), dtype=torch.uint8, device="cuda")
+    outs = []
+    for _ in range(2):
+        g = [torch.empty_like(x) for x in (Qd, Kd, Vd)]
+        scratch.fill_(255)
+        psa.psa_attention_bwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.lse, dO, *g, scratch)
+        torch.cuda.synchronize()
+        outs.append(g)
+    for x, y in zip(*outs):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
