@@ -46,6 +46,8 @@ def parse_args():
                     help="reorder Q, K, V along the Hilbert curve of the workload's token grid before the path and "
                          "restore the order of O after it (Sec. 3.3.1); the four row permutations are timed as "
                          "part of the step")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time psa_attention_bwd on the run's level map (outside the forward's timed region)")
     ap.add_argument("--no-threshold-point", action="store_true",
                     help="skip the second point with Alg. 2's threshold rule (tau = 0.5, 0.7, 0.8, 0.9)")
     return ap.parse_args()
@@ -396,6 +398,20 @@ def main():
             "attention_frac_of_peak": fl_t / (tmean[1] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "dense_equivalent_tflops": fl_dense / ((ms_pyr + tmean[0] + tmean[1]) * 1e-3) / 1e12,
         }
+    if args.backward:
+        # gradients under the budget rule's level map (the threshold point above has overwritten buf.M)
+        psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch)
+        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch, lse=buf.lse)
+        bscr = torch.empty(psa.psa_query_bwd_sizes(gp), dtype=torch.uint8, device="cuda")
+        dO = torch.randn_like(buf.O)
+        grads = [torch.empty_like(x) for x in (Qd, Kd, Vd)]
+        bcall = [lambda: psa.psa_attention_bwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.lse, dO, *grads, bscr)]
+        bcall[0]()
+        _, bmean, _ = timed_phases(torch, bcall, 3)
+        out["backward"] = {"attention_bwd_ms": bmean[0], "executed_tflop": 2.5 * fl_exec / 1e12,
+                           "achieved_tflops": 2.5 * fl_exec / (bmean[0] * 1e-3) / 1e12,
+                           "note": "fp32 vector-unit kernels (correctness-first path); FLOPs = 2.5 x the forward's executed FLOPs "
+                                   "(five products per kept pair instead of two)"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, budget, Q, K, V)
     print(json.dumps(out))

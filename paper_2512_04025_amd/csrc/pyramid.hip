@@ -30,59 +30,78 @@ struct SimArgs {
 };
 
 constexpr float COS_EPS = 1e-8f;   // cosine = dot / max(|a| |b|, COS_EPS): a zero key gives 0
-constexpr int SIM_MAX_TEAMS = 32;
 
-// sim_h(j), h = 2..H, of ONE key block (Alg. 3), by all `nthreads` threads of a workgroup.  A team of
-// `chunks` lanes (one 16-byte chunk of a row each) handles one token pair at a time; a team sums its
-// cosines in double, the teams' sums are added in a fixed order: the result does not depend on timing.
-// Reading: pairs (t, t + 2^(h-1)) with both tokens inside the block and the sequence; a block without
-// such a pair gets 1.  lds: bk floats (norms) followed by SIM_MAX_TEAMS * PSA_MAX_LEVELS doubles.
+// Dot product of `n16` consecutive 16-byte chunks of two rows: elements widened to fp32 (exact),
+// fp32 fused multiply-adds.  (The packed bfloat16 dot instruction was tried and is not used: its sums
+// came out up to several per cent off on this data.)
 template <typename T>
-__device__ void block_sims(const T* __restrict__ khead, int j, int N, int d, int bk, int H, int chunks,
-                           float* __restrict__ out, unsigned char* lds, int tid, int nthreads) {
+__device__ __forceinline__ float chunk_dot(const T* __restrict__ a, const T* __restrict__ b, int n16) {
+  constexpr int VEC = Elem<T>::VEC;
+  float acc = 0.f;
+  for (int x = 0; x < n16; ++x) {
+    float u[VEC], v[VEC];
+    Elem<T>::load(a + VEC * x, u);
+    Elem<T>::load(b + VEC * x, v);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc = fmaf(u[e], v[e], acc);
+  }
+  return acc;
+}
+
+// sim_h(j), h = 2..H, of ONE key block (Alg. 3), by the 256 threads of a workgroup.  Four lanes share
+// a token pair, each taking a quarter of the channels (coalesced 64- or 128-byte pieces of a row); the
+// norms of the block's tokens first, then every pair (t, t + 2^(h-1)), h ascending.  A slot (quad) sums
+// the cosines of its pairs in double, the 64 slots' sums are added in a fixed order: the result does
+// not depend on timing.  (One whole row per lane, all loads in flight at once, was measured slower:
+// the rows of neighbouring lanes are 256 bytes apart.)
+// Reading: pairs with both tokens inside the block and the sequence; a block without such a pair gets 1.
+// lds: bk floats (norms) followed by 64 * PSA_MAX_LEVELS doubles.
+template <typename T>
+__device__ void block_sims(const T* __restrict__ khead, int j, int N, int d, int bk, int H,
+                           float* __restrict__ out, unsigned char* lds, int tid) {
   constexpr int VEC = Elem<T>::VEC;
   float* nrm = reinterpret_cast<float*>(lds);
   double* part = reinterpret_cast<double*>(lds + (((size_t)bk * sizeof(float) + 15) & ~(size_t)15));
-  const int teams = nthreads / chunks, team = tid / chunks, tl = tid % chunks;
+  const int slot = tid >> 2, qd = tid & 3;
+  const int qlen = d / 4, n16 = qlen / VEC;       // channels and 16-byte chunks per quarter row
   const int lo = j * bk;
   int ntok = N - lo;
   ntok = ntok > bk ? bk : ntok;
-  auto team_sum = [&](float x) __attribute__((always_inline)) {
-    for (int off = chunks >> 1; off; off >>= 1) x += __shfl_xor(x, off, 64);
+  const T* base = khead + (int64_t)lo * d + qd * qlen;
+  auto quad_sum = [&](float x) __attribute__((always_inline)) {
+    x += __shfl_xor(x, 1, 64);
+    x += __shfl_xor(x, 2, 64);
     return x;
   };
   __syncthreads();                               // LDS may still be in use by the previous block
-  for (int t = team; t < ntok; t += teams) {
-    float a[VEC];
-    Elem<T>::load(khead + (int64_t)(lo + t) * d + tl * VEC, a);
-    float acc = 0.f;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc = fmaf(a[e], a[e], acc);
-    acc = team_sum(acc);
-    if (tl == 0) nrm[t] = sqrtf(acc);
+  for (int t = slot; t < ntok; t += 64) {
+    const float n2 = quad_sum(chunk_dot<T>(base + (int64_t)t * d, base + (int64_t)t * d, n16));
+    if (qd == 0) nrm[t] = sqrtf(n2);
   }
+  for (int x = tid; x < 64 * PSA_MAX_LEVELS; x += 256) part[x] = 0.0;
   __syncthreads();
-  for (int h = 2; h <= H; ++h) {
-    const int s = 1 << (h - 1);
-    double sum = 0.0;
-    for (int t = team; t + s < ntok; t += teams) {
-      float a[VEC], b[VEC];
-      Elem<T>::load(khead + (int64_t)(lo + t) * d + tl * VEC, a);
-      Elem<T>::load(khead + (int64_t)(lo + t + s) * d + tl * VEC, b);
-      float acc = 0.f;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) acc = fmaf(a[e], b[e], acc);
-      acc = team_sum(acc);
-      sum += (double)(acc / fmaxf(nrm[t] * nrm[t + s], COS_EPS));
+  // all pairs of all levels as one list, level by level: pair x of level h is (x, x + 2^(h-1))
+  int h = 2, first = 0, np = ntok - 2 > 0 ? ntok - 2 : 0;
+  double sum = 0.0;
+  for (int x = slot;; x += 64) {
+    while (h <= H && x >= first + np) {          // past the pairs of level h: hand its sum over
+      if (qd == 0) part[slot * PSA_MAX_LEVELS + (h - 2)] = sum;
+      sum = 0.0;
+      first += np;
+      ++h;
+      np = ntok - (1 << (h - 1));
+      np = np > 0 ? np : 0;
     }
-    if (tl == 0) part[team * PSA_MAX_LEVELS + (h - 2)] = sum;
+    if (h > H) break;
+    const int t = x - first, s = 1 << (h - 1);
+    const float dot = quad_sum(chunk_dot<T>(base + (int64_t)t * d, base + (int64_t)(t + s) * d, n16));
+    sum += (double)(dot / fmaxf(nrm[t] * nrm[t + s], COS_EPS));
   }
   __syncthreads();
   if (tid < H - 1) {
-    const int s = 1 << (tid + 1);
-    const int npairs = ntok - s;
+    const int npairs = ntok - (1 << (tid + 1));
     double tot = 0.0;
-    for (int t = 0; t < teams; ++t) tot += part[t * PSA_MAX_LEVELS + tid];
+    for (int u = 0; u < 64; ++u) tot += part[u * PSA_MAX_LEVELS + tid];
     out[tid] = npairs > 0 ? (float)(tot / (double)npairs) : 1.f;
   }
 }
@@ -176,8 +195,7 @@ __global__ __launch_bounds__(256) void pyramid_kernel(const T* __restrict__ K, c
       const int64_t hb = first + x;
       if (hb >= (int64_t)a.heads * a.nk) break;              // uniform over the workgroup
       const int bh = (int)(hb / a.nk), j = (int)(hb % a.nk);
-      block_sims<T>(K + (int64_t)bh * a.N * a.d, j, a.N, a.d, a.bk, H, a.chunks,
-                    sa.sims + hb * (H - 1), sim_lds, (int)threadIdx.x, 256);
+      block_sims<T>(K + (int64_t)bh * a.N * a.d, j, a.N, a.d, a.bk, H, sa.sims + hb * (H - 1), sim_lds, (int)threadIdx.x);
     }
     return;
   }
@@ -195,8 +213,7 @@ __global__ __launch_bounds__(256) void sims_kernel(const T* __restrict__ K, floa
                                                    int bk, int nk, int H, int chunks) {
   extern __shared__ __attribute__((aligned(16))) unsigned char sim_lds[];
   const int j = blockIdx.x, bh = blockIdx.y;
-  block_sims<T>(K + (int64_t)bh * N * d, j, N, d, bk, H, chunks, sims + ((int64_t)bh * nk + j) * (H - 1), sim_lds,
-                (int)threadIdx.x, 256);
+  block_sims<T>(K + (int64_t)bh * N * d, j, N, d, bk, H, sims + ((int64_t)bh * nk + j) * (H - 1), sim_lds, (int)threadIdx.x);
 }
 
 // L_j = max{1, h : sim_h(j) > tau_s^(h)} (Alg. 3: every level is tested).  all_heads: sim_h(j) is first
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(256) void cap_kernel(const float* __restrict__ sims
 }
 
 static size_t sims_lds_bytes(int bk) {
-  return (((size_t)bk * sizeof(float) + 15) & ~(size_t)15) + SIM_MAX_TEAMS * PSA_MAX_LEVELS * sizeof(double);
+  return (((size_t)bk * sizeof(float) + 15) & ~(size_t)15) + 64 * PSA_MAX_LEVELS * sizeof(double);
 }
 
 template <typename T>
