@@ -46,6 +46,9 @@ def parse_args():
                     help="reorder Q, K, V along the Hilbert curve of the workload's token grid before the path and "
                          "restore the order of O after it (Sec. 3.3.1); the four row permutations are timed as "
                          "part of the step")
+    ap.add_argument("--sim-cap", action="store_true",
+                    help="build the cosine-similarity level cap of App. B.1 in the pyramid pass (psa_build_pyramid_cap, "
+                         "thresholds 0.70, 0.65, 0.60 as printed for video generation) and feed it to the allocation")
     ap.add_argument("--backward", action="store_true",
                     help="also time psa_attention_bwd on the run's level map (outside the forward's timed region)")
     ap.add_argument("--no-threshold-point", action="store_true",
@@ -280,8 +283,21 @@ def main():
         for src, dst in zip(hil["raster"], (Qd, Kd, Vd)):
             psa.psa_permute_tokens(gp, src, hil["perm"], dst)
 
-    calls = [lambda: psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr),
-             lambda: psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho),
+    cap = None
+    if args.sim_cap and w.levels > 1:
+        tau_s = ((0.70, 0.65, 0.60) + (0.60,) * 8)[:w.levels - 1]
+        cap = {"tau_s": tau_s, "sim": torch.empty((w.B, w.Hkv, gp.nk, w.levels - 1), dtype=torch.float32, device="cuda"),
+               "L": torch.empty((w.B, w.Hkv, gp.nk), dtype=torch.uint8, device="cuda")}
+
+    def pyramid_call():
+        if cap:
+            psa.psa_build_pyramid_cap(gp, Kd, Vd, buf.Kpyr, buf.Vpyr, cap["tau_s"], cap["sim"], cap["L"])
+        else:
+            psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+
+    calls = [pyramid_call,
+             lambda: psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, rho_out=buf.rho,
+                                             level_cap=cap["L"] if cap else None),
              lambda: psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch)]
     if hil:
         calls = [permute_in] + calls + [lambda: psa.psa_permute_tokens(gp, buf.O, hil["perm"], hil["O"], inverse=True)]
@@ -341,6 +357,11 @@ def main():
             "note": "K, V read + pooled levels written + Q read + level-H keys read + S written and read + M written, "
                     "over the mean HIP-event time of the two calls"},
     }
+    if cap:
+        Lh = cap["L"].cpu().numpy()
+        out["config"]["similarity_cap"] = {"tau_s": list(cap["tau_s"]), "reduce": "per_head",
+                                           "level_cap_histogram": [int((Lh == h).sum()) for h in range(1, w.levels + 1)]}
+        out["roofline_pyramid"]["kernel"] = "pyramid_kernel with the similarities of Alg. 3 + cap_kernel"
     if hil:
         e = 2 if w.dtype == "bf16" else 4
         perm_bytes = 2.0 * e * w.N * w.d * w.B * (2 * w.Hq + 2 * w.Hkv)     # Q, K, V in and O out, each read and written once

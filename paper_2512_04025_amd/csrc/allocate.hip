@@ -78,73 +78,71 @@ __device__ __forceinline__ uint64_t lane_xor64(uint64_t v, int m) {
 // register between lanes l and l ^ m.  No LDS traffic and no barrier in the sort.
 // FACTORED: the scores are evaluated here from the matrix-core importance sweep's block maxima and
 // softmax statistics (max pooling of Eq. 4: S_ij = 2^(max over the block's 8 rows of (largest logit - lse)))
-// instead of being read from memory.
-template <int KPL, bool FACTORED>
-__global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, const uint8_t* __restrict__ cap,
-                                                   uint8_t* __restrict__ M, uint32_t* __restrict__ rowcnt,
-                                                   AllocArgs a) {
+// instead of being read from memory.  That part is plain streaming work, so the workgroup then has
+// four wavefronts: all of them evaluate the row into LDS (and write it out if the caller wants the
+// scores); with NW = 1 three then retire and the first sorts the row.
+// NW = 4 (rows of more than 1024 blocks): the row is spread over the 256 lanes of four wavefronts,
+// KPL keys each; the three merge steps whose partner lane sits in another wavefront go through LDS.
+// (One wavefront with 32 or 64 keys per lane needs 140+ registers: three wavefronts per SIMD, and the
+// sort, a chain of short dependent steps, then runs 6.8 times longer per row than with 16 keys per lane.)
+template <int KPL, bool FACTORED, int NW>
+__global__ __launch_bounds__((FACTORED || NW == 4) ? 256 : 64) void alloc_kernel(const float* __restrict__ S, const uint8_t* __restrict__ cap,
+                                                                    uint8_t* __restrict__ M, uint32_t* __restrict__ rowcnt,
+                                                                    AllocArgs a) {
   __shared__ int cnt_s[PSA_MAX_LEVELS + 1];
   __shared__ float lse_s[8];
-  const int lane = threadIdx.x;
+  __shared__ float srow_s[FACTORED ? KPL * 64 * NW : 1];
+  __shared__ uint64_t xbuf[NW == 4 ? KPL * 256 : 1];
+  __shared__ double wave_d[4];
+  __shared__ int wave_i[4];
+  constexpr int LANES = 64 * NW;
+  const int lane = threadIdx.x & 63;
+  const int glane = NW == 1 ? lane : (int)threadIdx.x;   // position of this lane among the sorting lanes
   const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
   const int64_t head = (int64_t)b * a.Hq + hq;
   const int64_t row = head * a.nq + i;
   const float* s_row = FACTORED ? nullptr : S + row * a.nk;
-  const float* bm0 = nullptr;
+  if (threadIdx.x <= PSA_MAX_LEVELS) cnt_s[threadIdx.x] = 0;
   if (FACTORED) {
-    if (lane < 8) {     // lse of the block's 8 representative rows from the key slices' partial results
-      const float2* pr = a.fs.part + ((head * a.nq + i) * 8 + lane) * 8;
+    const int tid = threadIdx.x;
+    if (tid < 8) {      // lse of the block's 8 representative rows from the key slices' partial results
+      const float2* pr = a.fs.part + ((head * a.nq + i) * 8 + tid) * 8;
       float mrow = -INFINITY, lrow = 0.f;
       for (int s2 = 0; s2 < a.fs.ksplit; ++s2) mrow = fmaxf(mrow, pr[s2].x);
       for (int s2 = 0; s2 < a.fs.ksplit; ++s2) {
         const float2 v = pr[s2];
         if (v.x != -INFINITY) lrow += v.y * __builtin_amdgcn_exp2f(v.x - mrow);
       }
-      lse_s[lane] = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;   // no visible key: all scores 0
+      lse_s[tid] = lrow > 0.f ? mrow + __log2f(lrow) : INFINITY;   // no visible key: all scores 0
     }
     __syncthreads();
-    bm0 = a.fs.bmax + (head * a.fs.bm_rows + (int64_t)i * 8) * a.fs.bm_pitch;
-  }
-  // FACTORED: the row's scores, block c*64 + lane in element c.  All loads first (8 rows x KPL per
-  // lane, no store in between for the compiler to order them against), then the optional write-out.
-  float sc[KPL];
-  if (FACTORED) {
+    const float* __restrict__ bm0 = a.fs.bmax + (head * a.fs.bm_rows + (int64_t)i * 8) * a.fs.bm_pitch;
+    for (int j = tid; j < a.nk; j += 256) {
+      float v = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < KPL; ++c) sc[c] = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const float* __restrict__ br = bm0 + (int64_t)r * a.fs.bm_pitch;
-      const float lr = lse_s[r];
-#pragma unroll
-      for (int c = 0; c < KPL; ++c) {
-        const int j = c * 64 + lane;
-        if (j < a.nk) sc[c] = fmaxf(sc[c], br[j] - lr);
-      }
+      for (int r = 0; r < 8; ++r) v = fmaxf(v, bm0[(int64_t)r * a.fs.bm_pitch + j] - lse_s[r]);
+      const float sc = __builtin_amdgcn_exp2f(v);
+      srow_s[j] = sc;
+      if (a.S_out) a.S_out[row * a.nk + j] = sc;
     }
-#pragma unroll
-    for (int c = 0; c < KPL; ++c) sc[c] = __builtin_amdgcn_exp2f(sc[c]);
-    if (a.S_out) {
-#pragma unroll
-      for (int c = 0; c < KPL; ++c) {
-        const int j = c * 64 + lane;
-        if (j < a.nk) a.S_out[row * a.nk + j] = sc[c];
-      }
-    }
+    __syncthreads();
+    if (NW == 1 && tid >= 64) return;   // no workgroup barrier follows in that instantiation
+  } else {
+    __syncthreads();
   }
   uint8_t* m_row = M + row * a.nk;
   const uint8_t* cap_row = cap ? cap + ((int64_t)b * a.Hkv + hq / (a.Hq / a.Hkv)) * a.nk : nullptr;
   const bool quota = a.mode != PSA_ALLOC_THRESHOLD;
 
-  if (lane <= PSA_MAX_LEVELS) cnt_s[lane] = 0;
   uint64_t key[KPL];
   int n_vis = 0;
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
-    const int j = r * 64 + lane;   // any initial placement will do; this one reads coalesced
+    const int j = r * LANES + glane;   // any initial placement will do; this one reads coalesced
     uint64_t kk = ~0ull;
     if (j < a.nk) {
       const int v = block_vis(i, j, a.bq, a.bk, a.N, a.causal);
-      const float sj = FACTORED ? sc[r] : (v != 0 ? s_row[j] : 0.f);
+      const float sj = FACTORED ? srow_s[j] : (v != 0 ? s_row[j] : 0.f);
       if (v == 0) {
         m_row[j] = 0;
       } else {
@@ -157,8 +155,13 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
   }
 #pragma unroll
   for (int off = 32; off; off >>= 1) n_vis += __shfl_xor(n_vis, off, 64);
+  if (NW == 4) {
+    if (lane == 0) wave_i[threadIdx.x >> 6] = n_vis;
+    __syncthreads();
+    n_vis = wave_i[0] + wave_i[1] + wave_i[2] + wave_i[3];
+  }
 
-  // bitonic sort, ascending over position lane*KPL + r
+  // bitonic sort, ascending over position glane*KPL + r
   auto in_lane = [&](uint64_t& x, uint64_t& y, bool up) {
     const bool sw = (x > y) == up;
     const uint64_t lo = sw ? y : x;
@@ -172,22 +175,35 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
 #pragma unroll
       for (int r = 0; r < KPL; ++r) {
         if (r & jj) continue;
-        const bool up = k < KPL ? ((r & k) == 0) : ((lane & 1) == 0);
+        const bool up = k < KPL ? ((r & k) == 0) : ((glane & 1) == 0);
         in_lane(key[r], key[r | jj], up);
       }
     }
   }
 #pragma unroll
-  for (int kl = 2; kl <= 64; kl <<= 1) {      // phase k = kl * KPL
-    const bool up = (lane & kl) == 0;
+  for (int kl = 2; kl <= LANES; kl <<= 1) {   // phase k = kl * KPL
+    const bool up = (glane & kl) == 0;
 #pragma unroll
     for (int m = kl >> 1; m > 0; m >>= 1) {   // partner lane l ^ m
-      const bool keep_min = ((lane & m) == 0) == up;
+      const bool keep_min = ((glane & m) == 0) == up;
+      if (m >= 64) {                          // the partner is in another wavefront: through LDS
 #pragma unroll
-      for (int r = 0; r < KPL; ++r) {
-        const uint64_t mine = key[r];
-        const uint64_t other = lane_xor64(mine, m);
-        key[r] = ((mine < other) == keep_min) ? mine : other;
+        for (int r = 0; r < KPL; ++r) xbuf[r * 256 + glane] = key[r];
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < KPL; ++r) {
+          const uint64_t mine = key[r];
+          const uint64_t other = xbuf[r * 256 + (glane ^ m)];
+          key[r] = ((mine < other) == keep_min) ? mine : other;
+        }
+        __syncthreads();
+      } else {
+#pragma unroll
+        for (int r = 0; r < KPL; ++r) {
+          const uint64_t mine = key[r];
+          const uint64_t other = lane_xor64(mine, m);
+          key[r] = ((mine < other) == keep_min) ? mine : other;
+        }
       }
     }
 #pragma unroll
@@ -200,7 +216,7 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
     }
   }
 
-  const int k0 = lane * KPL;
+  const int k0 = glane * KPL;
   int e_hi[PSA_MAX_LEVELS];
   double offset = 0.0, total = 1.0;
   bool uniform = false;
@@ -223,17 +239,28 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
     total = part;
 #pragma unroll
     for (int off = 32; off; off >>= 1) total += __shfl_xor(total, off, 64);
+    if (NW == 4) {
+      if (lane == 0) wave_d[threadIdx.x >> 6] = total;
+      __syncthreads();
+      total = ((wave_d[0] + wave_d[1]) + wave_d[2]) + wave_d[3];
+      __syncthreads();
+    }
     uniform = !(total > 0.0);
     if (uniform) total = (double)n_vis;
     double local = 0.0;
 #pragma unroll
     for (int r = 0; r < KPL; ++r)
       if (k0 + r < n_vis) local += (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(key[r] >> 32))) / total;
-    offset = wave_incl_scan(local, lane) - local;
+    const double incl = wave_incl_scan(local, lane);
+    offset = incl - local;
+    if (NW == 4) {                            // plus the shares held by the wavefronts before this one
+      if (lane == 63) wave_d[threadIdx.x >> 6] = incl;
+      __syncthreads();
+      for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) offset += wave_d[w];
+    }
   }
 
-  __syncthreads();   // the counters are zero
-  double run = 0.0;
+  double run = 0.0;               // (the counters were cleared before the first barrier)
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
     const int k = k0 + r;
@@ -259,16 +286,19 @@ __global__ __launch_bounds__(64) void alloc_kernel(const float* __restrict__ S, 
       atomicAdd(&cnt_s[level], 1);
     }
   }
-  __syncthreads();
-  if (lane <= a.H) rowcnt[row * ROWCNT_STRIDE + lane] = lane == 0 ? (uint32_t)n_vis : (uint32_t)cnt_s[lane];
+  // the counters are complete: one wavefront is left here in either instantiation and its LDS
+  // operations complete in order, so a fence is enough where the other wavefronts have retired
+  if (FACTORED && NW == 1) __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+  else __syncthreads();
+  if (glane <= a.H) rowcnt[row * ROWCNT_STRIDE + lane] = lane == 0 ? (uint32_t)n_vis : (uint32_t)cnt_s[lane];
 }
 
-template <int KPL>
+template <int KPL, int NW>
 static hipError_t launch_alloc_t(const Plan& pl, const AllocArgs& a, const float* S, const uint8_t* cap, uint8_t* M,
                                  uint32_t* rowcnt, hipStream_t s) {
   dim3 grid(pl.nq, pl.Hq, pl.B);
-  if (a.fs.bmax) alloc_kernel<KPL, true><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
-  else alloc_kernel<KPL, false><<<grid, 64, 0, s>>>(S, cap, M, rowcnt, a);
+  if (a.fs.bmax) alloc_kernel<KPL, true, NW><<<grid, 256, 0, s>>>(S, cap, M, rowcnt, a);
+  else alloc_kernel<KPL, false, NW><<<grid, 64 * NW, 0, s>>>(S, cap, M, rowcnt, a);
   return hipGetLastError();
 }
 
@@ -285,13 +315,13 @@ hipError_t launch_allocate(const Plan& pl, const float* S, const FactoredScores*
   int kpl = 1;                       // keys per lane: the row padded to a power of two >= 64
   while (64 * kpl < pl.nk) kpl <<= 1;
   switch (kpl) {
-    case 1:  return launch_alloc_t<1>(pl, a, S, cap, M, rowcnt, s);
-    case 2:  return launch_alloc_t<2>(pl, a, S, cap, M, rowcnt, s);
-    case 4:  return launch_alloc_t<4>(pl, a, S, cap, M, rowcnt, s);
-    case 8:  return launch_alloc_t<8>(pl, a, S, cap, M, rowcnt, s);
-    case 16: return launch_alloc_t<16>(pl, a, S, cap, M, rowcnt, s);
-    case 32: return launch_alloc_t<32>(pl, a, S, cap, M, rowcnt, s);
-    case 64: return launch_alloc_t<64>(pl, a, S, cap, M, rowcnt, s);
+    case 1:  return launch_alloc_t<1, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 2:  return launch_alloc_t<2, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 4:  return launch_alloc_t<4, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 8:  return launch_alloc_t<8, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 16: return launch_alloc_t<16, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 32: return launch_alloc_t<8, 4>(pl, a, S, cap, M, rowcnt, s);    // 2048 keys: 256 lanes x 8
+    case 64: return launch_alloc_t<16, 4>(pl, a, S, cap, M, rowcnt, s);   // 4096 keys: 256 lanes x 16
     default: return hipErrorInvalidValue;   // more than PSA_MAX_NK key blocks: refused before any launch
   }
 }
