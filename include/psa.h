@@ -40,7 +40,7 @@ enum { PSA_OK = 0, PSA_EINVAL = 1, PSA_EUNSUPPORTED = 2, PSA_ELAUNCH = 3 };
 enum { PSA_BF16 = 0, PSA_F32 = 1 };
 enum { PSA_REP_STRIDED = 0, PSA_REP_POOLED = 1 };
 enum { PSA_EST_MAX = 0, PSA_EST_MEAN = 1 };
-enum { PSA_ALLOC_THRESHOLD = 0, PSA_ALLOC_QUANTILE = 1, PSA_ALLOC_BUDGET = 2 };
+enum { PSA_ALLOC_THRESHOLD = 0, PSA_ALLOC_QUANTILE = 1, PSA_ALLOC_BUDGET = 2, PSA_ALLOC_THRESHOLD_EXCL = 3 };
 enum { PSA_CAP_PER_HEAD = 0, PSA_CAP_ALL_HEADS = 1 };
 
 #define PSA_MAX_LEVELS 8
@@ -58,8 +58,8 @@ typedef struct psa_params {
   int32_t rep_mode;         /* PSA_REP_STRIDED: token  start + floor((t+1/2) b/s);  PSA_REP_POOLED:     */
                             /* mean of the t-th of s contiguous groups (rounded to dtype)               */
   int32_t est_pool;         /* PSA_EST_MAX (Eq. 4) | PSA_EST_MEAN (App. B.2 variant)                    */
-  int32_t alloc_mode;       /* PSA_ALLOC_THRESHOLD (Alg. 2) | PSA_ALLOC_QUANTILE | PSA_ALLOC_BUDGET     */
-  float tau[PSA_MAX_LEVELS];/* THRESHOLD: tau_1 <= ... <= tau_H in [0,1] (Eq. 6).  QUANTILE: cumulative */
+  int32_t alloc_mode;       /* PSA_ALLOC_THRESHOLD (Alg. 2) | PSA_ALLOC_THRESHOLD_EXCL | _QUANTILE | _BUDGET */
+  float tau[PSA_MAX_LEVELS];/* THRESHOLD(_EXCL): tau_1 <= ... <= tau_H in [0,1] (Eq. 6).  QUANTILE: cumulative */
                             /* block fractions a_1 <= ... <= a_H in [0,1] (Sec. 4.4).  BUDGET: unused   */
   float budget;             /* BUDGET: target compute ratio rho-bar of Eq. 9, in (0, 1]                 */
 } psa_params;
@@ -142,7 +142,9 @@ int psa_build_pyramid_cap(const psa_params* p, const void* K, const void* V, voi
  *   block pair (i, j) of  Softmax_row(Q~ K~^T * scale), the softmax running over the representative
  *   keys of all key blocks.  Skipped when scores_in is given.
  *   Assignment:  THRESHOLD = Alg. 2 (row-normalise, stable descending sort, inclusive cumulative sum
- *   in fp64, M = min{t : S^ <= tau_t}, else 0);  QUANTILE = rank r gets min{h : r < floor(a_h n + 1e-3)};
+ *   in fp64, M = min{t : S^ <= tau_t}, else 0);  THRESHOLD_EXCL = the same with the exclusive cumulative
+ *   sum (the mass of the blocks ranked before this one: the kept blocks then cover at least tau_H of the
+ *   row, nucleus selection; the other reading of Alg. 2's "cumsum");  QUANTILE = rank r gets min{h : r < floor(a_h n + 1e-3)};
  *   BUDGET = QUANTILE with a_h derived from `budget` (level 1 gets 60 % of the budget FLOPs, levels
  *   2..H' share 40 % equally; H' the deepest level count whose quotas fit).  In every mode the
  *   top-ranked block of a row is kept (level 1) if the rule would skip it; causal: invisible blocks

@@ -49,7 +49,7 @@ class Params:
     sk: int = 0                      # representatives per key block; 0 -> bk >> (H-1)
     rep_mode: str = "pooled"         # "strided" (sampled tokens) | "pooled" (group means)
     est_pool: str = "max"            # "max" (Eq. 4) | "mean" (App. B.2 variant)
-    alloc_mode: str = "budget"       # "threshold" (Alg. 2) | "quantile" | "budget"
+    alloc_mode: str = "budget"       # "threshold" (Alg. 2) | "threshold_excl" | "quantile" | "budget"
     tau: Tuple[float, ...] = ()      # thresholds tau_1..tau_H, or cumulative cut points a_1..a_H
     budget: float = 0.25             # target rho-bar for "budget"
 
@@ -272,6 +272,7 @@ def allocate_row(s_row: np.ndarray, vis_row: np.ndarray, p: Params, cuts: Option
 
     threshold: Alg. 2 / Eq. 6-7 -- normalise the visible scores, sort descending (stable: ties keep
     the lower block index first), inclusive cumulative sum in fp64, M = min{t : E^ <= tau_t}, else 0.
+    threshold_excl: the same with the exclusive cumulative sum (the other way to read "cumsum" in Alg. 2).
     quantile / budget: ranks against cumulative cut points (Sec. 4.4's quantile rule).
     Guards (readings): if the rule would skip even the top-ranked block (e.g. a one-hot row under
     Alg. 2, whose share exceeds tau_H) that block is kept at level 1, so no row is empty; an all-zero
@@ -286,7 +287,7 @@ def allocate_row(s_row: np.ndarray, vis_row: np.ndarray, p: Params, cuts: Option
     if n_vis == 0:
         return out
     s = s_row[cols].astype(np.float32).astype(np.float64)
-    if p.alloc_mode == "threshold":
+    if p.alloc_mode in ("threshold", "threshold_excl"):
         total = s.sum()
         if not total > 0.0:
             s = np.ones_like(s)
@@ -294,6 +295,11 @@ def allocate_row(s_row: np.ndarray, vis_row: np.ndarray, p: Params, cuts: Option
         E = s / total
         order = np.argsort(-E, kind="stable")
         Ehat = np.cumsum(E[order])
+        if p.alloc_mode == "threshold_excl":
+            # variant reading of Alg. 2's cumulative sum: the mass of the blocks ranked BEFORE this one
+            # (a block is kept at level t while the blocks ahead of it have not yet covered tau_t, so the
+            # kept blocks cover at least tau_H of the row: nucleus / top-p selection)
+            Ehat = Ehat - E[order]
         tau = [float(np.float32(t)) for t in p.tau[:H]]
         lev_sorted = np.zeros(n_vis, dtype=np.uint8)
         for k in range(n_vis):

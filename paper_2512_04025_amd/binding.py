@@ -9,7 +9,7 @@ PSA_OK, PSA_EINVAL, PSA_EUNSUPPORTED, PSA_ELAUNCH = 0, 1, 2, 3
 PSA_BF16, PSA_F32 = 0, 1
 PSA_REP_STRIDED, PSA_REP_POOLED = 0, 1
 PSA_EST_MAX, PSA_EST_MEAN = 0, 1
-PSA_ALLOC_THRESHOLD, PSA_ALLOC_QUANTILE, PSA_ALLOC_BUDGET = 0, 1, 2
+PSA_ALLOC_THRESHOLD, PSA_ALLOC_QUANTILE, PSA_ALLOC_BUDGET, PSA_ALLOC_THRESHOLD_EXCL = 0, 1, 2, 3
 PSA_CAP_PER_HEAD, PSA_CAP_ALL_HEADS = 0, 1
 PSA_MAX_LEVELS = 8
 

@@ -132,7 +132,8 @@ __global__ __launch_bounds__((FACTORED || NW == 4) ? 256 : 64) void alloc_kernel
   }
   uint8_t* m_row = M + row * a.nk;
   const uint8_t* cap_row = cap ? cap + ((int64_t)b * a.Hkv + hq / (a.Hq / a.Hkv)) * a.nk : nullptr;
-  const bool quota = a.mode != PSA_ALLOC_THRESHOLD;
+  const bool quota = a.mode != PSA_ALLOC_THRESHOLD && a.mode != PSA_ALLOC_THRESHOLD_EXCL;
+  const bool exclusive = a.mode == PSA_ALLOC_THRESHOLD_EXCL;   // Alg. 2 read with the exclusive cumulative sum
 
   uint64_t key[KPL];
   int n_vis = 0;
@@ -271,8 +272,9 @@ __global__ __launch_bounds__((FACTORED || NW == 4) ? 256 : 64) void alloc_kernel
         for (int h = a.H - 1; h >= 0; --h)
           if (k < e_hi[h]) level = h + 1;
       } else {
-        run += (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(key[r] >> 32))) / total;
-        const double ehat = offset + run;
+        const double share = (uniform ? 1.0 : (double)from_desc_bits((uint32_t)(key[r] >> 32))) / total;
+        run += share;
+        const double ehat = exclusive ? (offset + run) - share : offset + run;
         for (int h = a.H - 1; h >= 0; --h)
           if (ehat <= (double)a.tau[h]) level = h + 1;
         if (k == 0 && level == 0) level = 1;

@@ -97,7 +97,7 @@ int make_plan(const psa_params* p, Plan* o) {
 // count whose block fractions sum to at most 1.
 static int plan_allocation(const psa_params* p, Plan* o) {
   const int H = o->H;
-  if (p->alloc_mode == PSA_ALLOC_THRESHOLD || p->alloc_mode == PSA_ALLOC_QUANTILE) {
+  if (p->alloc_mode == PSA_ALLOC_THRESHOLD || p->alloc_mode == PSA_ALLOC_THRESHOLD_EXCL || p->alloc_mode == PSA_ALLOC_QUANTILE) {
     float prev = 0.f;
     for (int h = 0; h < H; ++h) {
       const float t = p->tau[h];

@@ -11,7 +11,7 @@ from paper_2512_04025_amd.plumbing import Buffers, from_dev, to_dev  # noqa: F40
 
 _REP = {"strided": psa.PSA_REP_STRIDED, "pooled": psa.PSA_REP_POOLED}
 _EST = {"max": psa.PSA_EST_MAX, "mean": psa.PSA_EST_MEAN}
-_ALLOC = {"threshold": psa.PSA_ALLOC_THRESHOLD, "quantile": psa.PSA_ALLOC_QUANTILE, "budget": psa.PSA_ALLOC_BUDGET}
+_ALLOC = {"threshold": psa.PSA_ALLOC_THRESHOLD, "threshold_excl": psa.PSA_ALLOC_THRESHOLD_EXCL, "quantile": psa.PSA_ALLOC_QUANTILE, "budget": psa.PSA_ALLOC_BUDGET}
 
 
 def oracle_params(w: si.Workload, **over) -> Params:

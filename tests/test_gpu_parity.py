@@ -165,9 +165,11 @@ def _check_level_map(got, ref, S, op):
         row = S[b, h, i].astype(np.float64)
         near_score = np.abs(row - row[j]) <= 1e-6 * max(row.max(), 1e-30)
         tie = near_score.sum() > 1
-        if op.alloc_mode == "threshold" and not tie:
+        if op.alloc_mode in ("threshold", "threshold_excl") and not tie:
             order = np.argsort(-row, kind="stable")
             ehat = np.cumsum(row[order] / row.sum())
+            if op.alloc_mode == "threshold_excl":
+                ehat = ehat - row[order] / row.sum()
             k = int(np.nonzero(order == j)[0][0])
             tie = any(abs(ehat[k] - t) <= 1e-6 for t in tau)
         assert tie, f"level map differs at {(b, h, i, j)}: gpu {got[b, h, i, j]} oracle {ref[b, h, i, j]}"
@@ -184,6 +186,9 @@ def _check_level_map(got, ref, S, op):
     ("dit_small", dict(alloc_mode="quantile", tau=(0.15, 0.25, 0.45, 0.45))),
     ("vlm_small", dict(budget=0.25)),
     ("vlm_ragged", dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.8, 0.9))),
+    ("tiny", dict(alloc_mode="threshold_excl", tau=(0.7, 0.8, 0.9, 0.9))),
+    ("dit_small", dict(alloc_mode="threshold_excl", tau=(0.5, 0.7, 0.8, 0.9))),
+    ("vlm_ragged", dict(alloc_mode="threshold_excl", tau=(0.5, 0.7, 0.8, 0.9))),
     ("stress_small", dict(budget=0.3)),
     ("stress_small", dict(budget=0.5)),
     ("stress_small", dict(budget=1.0)),
@@ -209,7 +214,8 @@ def test_level_map_every_sort_width(nk):
     import torch
     w = si.small_variant(si.CONFIGS["dit1p3b"], nk * 32 - 7, Hq=1, Hkv=1).with_(bq=1024, bk=32, levels=3)
     rng = np.random.default_rng(nk)
-    for over in (dict(budget=0.3), dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.9)), dict(budget=0.2, causal=True)):
+    for over in (dict(budget=0.3), dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.9)), dict(budget=0.2, causal=True),
+                 dict(alloc_mode="threshold_excl", tau=(0.5, 0.7, 0.9), causal=True)):
         causal = over.pop("causal", False)
         op = oracle_params(w.with_(causal=causal), **over)
         gp = gpu_params(op)
@@ -392,7 +398,8 @@ def test_all_level1_mask_equals_dense_ref():
 @pytest.mark.parametrize("name,over", [("tiny", {}), ("dit_small", dict(budget=0.2)), ("vlm_small", {}),
                                        ("stress_small", dict(budget=0.2)), ("dit_n2000", dict(budget=0.2)),
                                        ("dit_n2000", dict(budget=0.2, est_pool="mean")),
-                                       ("dit_small", dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.8, 0.9)))])
+                                       ("dit_small", dict(alloc_mode="threshold", tau=(0.5, 0.7, 0.8, 0.9))),
+                                       ("dit_small", dict(alloc_mode="threshold_excl", tau=(0.5, 0.7, 0.8, 0.9)))])
 def test_whole_path_matches_oracle(name, over):
     """build_pyramid -> allocate_levels (own scores) -> attention_fwd, as the benchmark runs it.  The
     level map may differ from the oracle's only where rounding of the scores swaps near-tied ranks;

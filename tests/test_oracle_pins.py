@@ -682,3 +682,33 @@ def test_backward_all_level1_is_dense_attention_backward():
     dQ, dK, dV = orc.psa_attention_backward(Q, orc.build_pyramid(K, p), orc.build_pyramid(V, p), M, dO, p)
     for got, want in ((dQ, tq.grad), (dK, tk.grad), (dV, tv.grad)):
         np.testing.assert_allclose(got, want.numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- Alg. 2 with the exclusive cumulative sum
+def test_exclusive_cumsum_variant_hand_computed():
+    """Ten equal scores, tau = (0.25, 0.5): shares 0.1 each.  Inclusive sums 0.1, 0.2, 0.3 ...: two blocks
+    at level 1, three at level 2.  Exclusive sums 0, 0.1, 0.2 ...: three at level 1, three at level 2
+    (the block whose predecessors cover exactly 0.5 is still kept)."""
+    s = np.full(10, 2.0, dtype=np.float32)
+    vis = np.ones(10, dtype=np.uint8)
+    p = Params(1, 1, 1, 80, 4, 8, 8, 2, alloc_mode="threshold", tau=(0.25, 0.5))
+    assert orc.allocate_row(s, vis, p, None).tolist() == [1, 1, 2, 2, 2, 0, 0, 0, 0, 0]
+    p = Params(1, 1, 1, 80, 4, 8, 8, 2, alloc_mode="threshold_excl", tau=(0.25, 0.5))
+    assert orc.allocate_row(s, vis, p, None).tolist() == [1, 1, 1, 2, 2, 2, 0, 0, 0, 0]
+    onehot = np.zeros(10, dtype=np.float32)
+    onehot[7] = 5.0
+    assert orc.allocate_row(onehot, vis, p, None).tolist() == [0] * 7 + [1, 0, 0]
+
+
+def test_exclusive_cumsum_variant_covers_the_threshold_mass():
+    """Top-p property: the kept blocks of a row hold at least tau_H of its mass, and dropping the
+    lowest-ranked kept block would leave less than tau_H."""
+    rng = np.random.default_rng(12)
+    p = Params(1, 1, 1, 64 * 40, 4, 64, 64, 3, alloc_mode="threshold_excl", tau=(0.4, 0.6, 0.8))
+    for _ in range(20):
+        s = (rng.random(40) ** 5).astype(np.float32)
+        lev = orc.allocate_row(s, np.ones(40, dtype=np.uint8), p, None)
+        share = s.astype(np.float64) / s.astype(np.float64).sum()
+        kept = share[lev > 0]
+        assert kept.sum() >= 0.8 - 1e-12 and kept.sum() - kept.min() < 0.8
+        assert np.all(np.diff(lev[np.argsort(-share, kind="stable")][: (lev > 0).sum()].astype(int)) >= 0)
