@@ -431,7 +431,8 @@ def main():
         _, bmean, _ = timed_phases(torch, bcall, 3)
         out["backward"] = {"attention_bwd_ms": bmean[0], "executed_tflop": 2.5 * fl_exec / 1e12,
                            "achieved_tflops": 2.5 * fl_exec / (bmean[0] * 1e-3) / 1e12,
-                           "note": "fp32 vector-unit kernels (correctness-first path); FLOPs = 2.5 x the forward's executed FLOPs "
+                           "frac_of_bf16_mfma_peak": 2.5 * fl_exec / (bmean[0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                           "note": "bf16: matrix-core kernels for dQ and the pooled dK, dV; FLOPs = 2.5 x the forward's executed FLOPs "
                                    "(five products per kept pair instead of two)"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, budget, Q, K, V)

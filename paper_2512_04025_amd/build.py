@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libpsa.so")
-SOURCES = ["api.hip", "pyramid.hip", "importance.hip", "allocate.hip", "attn_rows.hip", "attn_mfma.hip", "attn_bwd.hip", "hilbert.hip", "probes.hip"]
+SOURCES = ["api.hip", "pyramid.hip", "importance.hip", "allocate.hip", "attn_rows.hip", "attn_mfma.hip", "attn_bwd.hip", "attn_bwd_mfma.hip", "hilbert.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          # packed-fp32 VALU forms are kept out of the generated code on purpose

@@ -339,7 +339,7 @@ int psa_attention_bwd(const psa_params* p, const void* Q, const void* K, const v
   const hipError_t e = launch_attn_bwd(pl, Q, K, V, Kpyr, Vpyr, M, idx, cnt, O, lse, dO,
                                        reinterpret_cast<float*>(at(scratch, l.off_D)),
                                        reinterpret_cast<float*>(at(scratch, l.off_dkp)),
-                                       reinterpret_cast<float*>(at(scratch, l.off_dvp)), dQ, dK, dV, s);
+                                       reinterpret_cast<float*>(at(scratch, l.off_dvp)), dQ, dK, dV, false, s);
   return e == hipSuccess ? PSA_OK : PSA_ELAUNCH;
 }
 

@@ -290,6 +290,11 @@ __global__ __launch_bounds__(256) void unpool_kernel(const float* __restrict__ d
   for (int u = 0; u < 4; ++u) o[u] = Elem<T>::from_f32(acc[u]);
 }
 
+bool bwd_uses_mfma(const Plan& pl);
+hipError_t launch_attn_bwd_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
+                                const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const float* lse, const void* dO,
+                                const float* Dr, float* dKp, float* dVp, void* dQ, hipStream_t s);
+
 size_t bwd_pooled_grad_elems(const Plan& pl) {      // one tensor: levels 1..H
   size_t n = 0;
   for (int h = 1; h <= pl.H; ++h) n += (size_t)pl.B * pl.Hkv * pl.nk * (pl.bk >> (h - 1)) * pl.d;
@@ -299,7 +304,8 @@ size_t bwd_pooled_grad_elems(const Plan& pl) {      // one tensor: levels 1..H
 template <typename T, int D>
 static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
                                const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const void* O, const float* lse,
-                               const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, hipStream_t s) {
+                               const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, bool use_mfma,
+                               hipStream_t s) {
   BwdArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.H = pl.H; a.causal = pl.causal; a.scale = pl.scale;
@@ -319,17 +325,22 @@ static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, con
   rowdot_kernel<T><<<(unsigned)((rows + 63) / 64), 256, 0, s>>>(go, static_cast<const T*>(O), Dr, rows, pl.d);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int slices = (pl.bq + 63) / 64;
-  bwd_dq_kernel<T, D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, 0, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
-                                                                        static_cast<T*>(dQ), a);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  for (int h = 1; h <= pl.H; ++h) {
-    int threads = 4 * (pl.bk >> (h - 1));
-    threads = threads < 64 ? 64 : threads;
-    bwd_dkv_kernel<T, D><<<dim3(pl.nk, pl.Hkv, pl.B), threads, 0, s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
+  if (use_mfma) {     // bfloat16: dQ and the pooled gradients on the matrix cores
+    e = launch_attn_bwd_mfma(pl, Q, K, V, Kp, Vp, M, idx, cnt, lse, dO, Dr, dKp, dVp, dQ, s);
+    if (e != hipSuccess) return e;
+  } else {
+    const int slices = (pl.bq + 63) / 64;
+    bwd_dq_kernel<T, D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, 0, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
+                                                                          static_cast<T*>(dQ), a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    for (int h = 1; h <= pl.H; ++h) {
+      int threads = 4 * (pl.bk >> (h - 1));
+      threads = threads < 64 ? 64 : threads;
+      bwd_dkv_kernel<T, D><<<dim3(pl.nk, pl.Hkv, pl.B), threads, 0, s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
   }
   const int heads = pl.B * pl.Hkv;
   const int64_t n = (int64_t)heads * pl.N * (pl.d / 4);
@@ -340,12 +351,14 @@ static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, con
 
 hipError_t launch_attn_bwd(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
                            const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const void* O, const float* lse,
-                           const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, hipStream_t s) {
+                           const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, bool vector_unit,
+                           hipStream_t s) {
   if (pl.dtype == PSA_F32)
-    return pl.d == 64 ? launch_bwd_t<float, 64>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, s)
-                      : launch_bwd_t<float, 128>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, s);
-  return pl.d == 64 ? launch_bwd_t<bf16_t, 64>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, s)
-                    : launch_bwd_t<bf16_t, 128>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, s);
+    return pl.d == 64 ? launch_bwd_t<float, 64>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, false, s)
+                      : launch_bwd_t<float, 128>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, false, s);
+  const bool mfma = !vector_unit && bwd_uses_mfma(pl);
+  return pl.d == 64 ? launch_bwd_t<bf16_t, 64>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, mfma, s)
+                    : launch_bwd_t<bf16_t, 128>(pl, Q, K, V, Kp, Vp, M, idx, cnt, O, lse, dO, Dr, dKp, dVp, dQ, dK, dV, mfma, s);
 }
 
 }  // namespace psa

@@ -1,0 +1,413 @@
+// Backward pass of the adaptive pyramid attention on the gfx950 matrix cores, bfloat16 (the chain rule
+// through Eq. 8 and the mean pooling of Eq. 2-3; see attn_bwd.hip for the formulas and for the fp32
+// vector-unit version that serves float32 and the shapes this one does not take).
+//
+// Two kernels, both on 32x32x16 MFMAs with fp32 accumulation, P and dS rounded to bfloat16 for the
+// products that consume them, no atomics:
+//   bwd_dq_mfma_kernel   one workgroup per 128 query rows (a wavefront per 32), walking the row's
+//        level-sorted block list in tiles of 64 pooled keys gathered into LDS.  Same operand roles as the
+//        forward kernel: S^T = Kbar Q^T and dP^T = Vbar dO^T put one query row in each lane (lse and
+//        D = dO.O are per-lane scalars), dS^T is packed in registers as the B operand of
+//        dQ^T += Kbar^T dS^T, whose A operand is read from the row-major Kbar tile with the transposing
+//        LDS load.
+//   bwd_dkv_mfma_kernel  the same with queries and keys exchanged: one workgroup per (key block, key
+//        head, level); the block's pooled keys and values sit in registers as B operands (one key per
+//        lane), the query blocks that use this block at this level (a walk down the level map's
+//        column, for every query head of the group) are staged through LDS 128 rows at a time;
+//        S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and dKbar^T += Q^T dS with the
+//        transposing load on the staged dO and Q.  The four wavefronts split the key halves and the
+//        row chunks between them and add their partial sums through LDS at the end.
+// LDS rows carry 16 bytes of padding, which spreads the rows of an operand read over all banks.
+#include "psa_dev.h"
+#include "psa_internal.h"
+
+namespace psa {
+
+struct BwdMfmaArgs {
+  int N, Hq, Hkv, nq, nk, bq, bk, lg_bk, H, causal;
+  float scale, scale_log2;
+  int64_t lvl_off[PSA_MAX_LEVELS + 2];   // level h >= 2 inside one pyramid buffer (elements)
+  int64_t glvl_off[PSA_MAX_LEVELS + 2];  // level h >= 1 inside one pooled-gradient buffer (elements)
+};
+
+typedef __attribute__((ext_vector_type(4))) short bs16x4;
+typedef __attribute__((ext_vector_type(8))) short bs16x8;
+typedef __attribute__((address_space(3))) bs16x4 lds_bs16x4;
+
+constexpr float LOG2E = 1.44269504088896340736f;
+
+// A operand [32 x 16] whose rows are the lanes' own rows of a row-major LDS tile: row `row`, the 16
+// bytes at channel k0 + hf * 8
+__device__ __forceinline__ bf16x8 frag_rows(const unsigned char* tile, int pitch, int row, int k0, int hf) {
+  return *reinterpret_cast<const bf16x8*>(tile + row * pitch + (k0 + hf * 8) * 2);
+}
+
+// A operand [32 channels x 16 rows] = the transpose of rows r0 .. r0+15, channels c0 .. c0+31 of a
+// row-major LDS tile, through the transposing load: the 16 lanes of a group address 4 rows x 32 bytes
+// and lane s of the group receives channel s of those rows; lane (l32, hf) ends up with channel
+// c0 + l32 of rows r0 + hf*4 + {0..3} and r0 + 8 + hf*4 + {0..3}: the order in which pack_b lays the
+// contraction index out.
+__device__ __forceinline__ bf16x8 frag_transposed(const unsigned char* tile, int pitch, int r0, int c0, int lane) {
+  const int grp = lane >> 4, s16 = lane & 15;
+  const int row = r0 + (lane >> 5) * 4 + (s16 >> 2);
+  const int byte = (c0 + (grp & 1) * 16 + (s16 & 3) * 4) * 2;
+  const unsigned char* p = tile + row * pitch + byte;
+  const bs16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_bs16x4*)(p));
+  const bs16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_bs16x4*)(p + 8 * pitch));
+  return __builtin_bit_cast(bf16x8, (bs16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// 16 accumulator values of one lane (rows (v/4)*8 + hf*4 + v%4 of a 32-row result) -> the two B
+// operands of the next product, whose contraction index runs over those 32 rows
+__device__ __forceinline__ void pack_b(const float (&x)[16], bf16x8& f0, bf16x8& f1) {
+#pragma unroll
+  for (int v = 0; v < 8; ++v) {
+    f0[v] = (__bf16)x[v];
+    f1[v] = (__bf16)x[8 + v];
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                          const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
+                                                          const bf16_t* __restrict__ Vp, const uint16_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ cnt, const float* __restrict__ lse,
+                                                          const float* __restrict__ Dr, const bf16_t* __restrict__ dO,
+                                                          bf16_t* __restrict__ dQ, BwdMfmaArgs a) {
+  constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32;
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[64 * PITCH];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[64 * PITCH];
+  __shared__ float term_s[64];
+  __shared__ int last_s[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int slices = (a.bq + 127) / 128;
+  const int i = blockIdx.x / slices, slice = blockIdx.x % slices;
+  const int hq = blockIdx.y, b = blockIdx.z;
+  const int hk = hq / (a.Hq / a.Hkv);
+  const int64_t qhead = (int64_t)b * a.Hq + hq, khead = (int64_t)b * a.Hkv + hk;
+  int row_end = (i + 1) * a.bq;
+  row_end = row_end < a.N ? row_end : a.N;
+  const int qrow = i * a.bq + slice * 128 + wave * 32 + l32;
+  const bool active = qrow < row_end;
+
+  bf16x8 qf[KS], gf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 x = {0u, 0u, 0u, 0u}, y = {0u, 0u, 0u, 0u};
+    if (active) {
+      x = *reinterpret_cast<const u32x4*>(Q + (qhead * a.N + qrow) * D + ks * 16 + hf * 8);
+      y = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + qrow) * D + ks * 16 + hf * 8);
+    }
+    qf[ks] = __builtin_bit_cast(bf16x8, x);
+    gf[ks] = __builtin_bit_cast(bf16x8, y);
+  }
+  const float lse2 = active ? lse[qhead * a.N + qrow] * LOG2E : INFINITY;   // inactive rows: every weight 0
+  const float my_D = active ? Dr[qhead * a.N + qrow] : 0.f;
+  f32x16 dq[MD];
+#pragma unroll
+  for (int md = 0; md < MD; ++md)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dq[md][v] = 0.f;
+
+  const int64_t srow = qhead * a.nq + i;
+  const uint16_t* my_idx = idx + srow * a.nk;
+  const int32_t* my_cnt = cnt + srow * CNT_STRIDE;
+  int lvl_start = 0;
+  for (int h = 1; h <= a.H; ++h) {
+    const int nblk = my_cnt[h - 1];
+    const int lg_th = a.lg_bk - (h - 1), th = 1 << lg_th, span = 1 << (h - 1);
+    const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
+    const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
+    const int ntl = ((nblk << lg_th) + 63) >> 6;
+    for (int tl = 0; tl < ntl; ++tl) {
+      __syncthreads();                           // the previous tile has been consumed
+      // gather the tile: row r of the tile is pooled row (block id << lg_th) | (stream position & (th-1))
+#pragma unroll
+      for (int c = 0; c < 64 * CPR / 256; ++c) {
+        const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+        const int g = (tl << 6) + r, e = g >> lg_th;
+        u32x4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
+        if (e < nblk) {
+          const int prow = ((int)my_idx[lvl_start + e] << lg_th) | (g & (th - 1));
+          if (prow * span < a.N) {
+            kv = *reinterpret_cast<const u32x4*>(kbase + (int64_t)prow * D + ch * 8);
+            vv = *reinterpret_cast<const u32x4*>(vbase + (int64_t)prow * D + ch * 8);
+          }
+        }
+        *reinterpret_cast<u32x4*>(Ks + r * PITCH + ch * 16) = kv;
+        *reinterpret_cast<u32x4*>(Vs + r * PITCH + ch * 16) = vv;
+      }
+      if (tid < 64) {
+        const int g = (tl << 6) + tid, e = g >> lg_th;
+        float term = -INFINITY;
+        int last = 0;
+        if (e < nblk) {
+          const int prow = ((int)my_idx[lvl_start + e] << lg_th) | (g & (th - 1));
+          const int first = prow * span;
+          int c = a.N - first;
+          c = c < 0 ? 0 : (c > span ? span : c);
+          if (c > 0) term = __log2f((float)c);
+          last = first + (c > 0 ? c : 1) - 1;
+        }
+        term_s[tid] = term;
+        last_s[tid] = last;
+      }
+      __syncthreads();
+      bf16x8 dsf[4];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        f32x16 sc, dp;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, PITCH, mb * 32 + l32, ks * 16, hf), qf[ks], sc, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, PITCH, mb * 32 + l32, ks * 16, hf), gf[ks], dp, 0, 0, 0);
+        }
+        float ds[16];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int col = mb * 32 + g4 * 8 + hf * 4;
+          const f32x4 tm = *reinterpret_cast<const f32x4*>(term_s + col);
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, tm[e4]) - lse2;
+            if (a.causal && last_s[col + e4] > qrow) x = -INFINITY;
+            const float p = __builtin_amdgcn_exp2f(x);
+            ds[g4 * 4 + e4] = p * (dp[g4 * 4 + e4] - my_D);
+          }
+        }
+        pack_b(ds, dsf[2 * mb], dsf[2 * mb + 1]);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int md = 0; md < MD; ++md)
+          dq[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Ks, PITCH, ks * 16, md * 32, lane), dsf[ks], dq[md], 0, 0, 0);
+    }
+    lvl_start += nblk;
+  }
+  if (active) {
+    bf16_t* op = dQ + (qhead * a.N + qrow) * D;
+#pragma unroll
+    for (int md = 0; md < MD; ++md)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(dq[md][4 * g + e] * a.scale);
+        *reinterpret_cast<bf16x4*>(op + md * 32 + g * 8 + hf * 4) = w;
+      }
+  }
+}
+
+// KH: 32-key groups of the block at this level (1, 2 or 4); the 4 / KH wavefronts that share a key
+// group split the 32-row chunks of every staged query tile between them.
+template <int D, int KH>
+__global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                           const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
+                                                           const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M,
+                                                           const float* __restrict__ lse, const float* __restrict__ Dr,
+                                                           const bf16_t* __restrict__ dO, float* __restrict__ dKp,
+                                                           float* __restrict__ dVp, int h, BwdMfmaArgs a) {
+  constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32, RH = 4 / KH;
+  constexpr int TILEB = 128 * PITCH;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* Qs = smem;                       // [128][PITCH]
+  unsigned char* Gs = smem + TILEB;               // [128][PITCH]
+  float* lse_s = reinterpret_cast<float*>(smem + 2 * TILEB);   // [128], log2 domain, +inf for rows that do not exist
+  float* D_s = lse_s + 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int kh = wave % KH, rh = wave / KH;
+  const int j = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int lg_th = a.lg_bk - (h - 1), th = 1 << lg_th, span = 1 << (h - 1);
+  const int group = a.Hq / a.Hkv;
+  const int64_t khead = (int64_t)b * a.Hkv + hk;
+  const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
+  const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
+
+  // this lane's pooled key (B operands of both first products): key kh*32 + l32 of the block
+  const int key = kh * 32 + l32;
+  const int prow = (j << lg_th) + key;
+  const int first = prow * span;
+  int ctok = a.N - first;
+  ctok = ctok < 0 ? 0 : (ctok > span ? span : ctok);
+  const bool valid = key < th && ctok > 0;
+  const float bias2 = valid ? __log2f((float)ctok) : -INFINITY;
+  const int last = first + (ctok > 0 ? ctok : 1) - 1;
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    u32x4 x = {0u, 0u, 0u, 0u}, y = {0u, 0u, 0u, 0u};
+    if (valid) {
+      x = *reinterpret_cast<const u32x4*>(kbase + (int64_t)prow * D + ks * 16 + hf * 8);
+      y = *reinterpret_cast<const u32x4*>(vbase + (int64_t)prow * D + ks * 16 + hf * 8);
+    }
+    kf[ks] = __builtin_bit_cast(bf16x8, x);
+    vf[ks] = __builtin_bit_cast(bf16x8, y);
+  }
+  f32x16 dk[MD], dv[MD];
+#pragma unroll
+  for (int md = 0; md < MD; ++md)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[md][v] = 0.f; dv[md][v] = 0.f; }
+
+  for (int gq = 0; gq < group; ++gq) {
+    const int hq = hk * group + gq;
+    const int64_t qhead = (int64_t)b * a.Hq + hq;
+    const uint8_t* mcol = M + (qhead * a.nq) * a.nk + j;
+    for (int i = 0; i < a.nq; ++i) {
+      if ((int)mcol[(int64_t)i * a.nk] != h) continue;              // uniform over the workgroup
+      int row_end = (i + 1) * a.bq;
+      row_end = row_end < a.N ? row_end : a.N;
+      for (int r0 = i * a.bq; r0 < row_end; r0 += 128) {
+        const int seg = row_end - r0 < 128 ? row_end - r0 : 128;
+        __syncthreads();                           // the previous tile has been consumed
+#pragma unroll
+        for (int c = 0; c < 128 * CPR / 256; ++c) {
+          const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+          u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
+          if (r < seg) {
+            qv = *reinterpret_cast<const u32x4*>(Q + (qhead * a.N + r0 + r) * D + ch * 8);
+            gv = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + r0 + r) * D + ch * 8);
+          }
+          *reinterpret_cast<u32x4*>(Qs + r * PITCH + ch * 16) = qv;
+          *reinterpret_cast<u32x4*>(Gs + r * PITCH + ch * 16) = gv;
+        }
+        if (tid < 128) {
+          lse_s[tid] = tid < seg ? lse[qhead * a.N + r0 + tid] * LOG2E : INFINITY;
+          D_s[tid] = tid < seg ? Dr[qhead * a.N + r0 + tid] : 0.f;
+        }
+        __syncthreads();
+        for (int c = rh; c * 32 < seg; c += RH) {  // this wavefront's 32-row chunks
+          f32x16 sc, dp;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
+          }
+          // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
+          float p[16], ds[16];
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            const int r = c * 32 + g4 * 8 + hf * 4;
+            const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
+            const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+              float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias2) - ls[e4];
+              if (a.causal && last > r0 + r + e4) x = -INFINITY;
+              const float pv = __builtin_amdgcn_exp2f(x);
+              p[g4 * 4 + e4] = pv;
+              ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
+            }
+          }
+          bf16x8 pf[2], dsf[2];
+          pack_b(p, pf[0], pf[1]);
+          pack_b(ds, dsf[0], dsf[1]);
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int md = 0; md < MD; ++md) {
+              dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
+              dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
+            }
+        }
+      }
+    }
+  }
+  // partial sums of the wavefronts that share a key group -> LDS [wavefront][key][channel], added in a
+  // fixed order; lane (key, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
+  float* red = reinterpret_cast<float*>(smem);    // 4 x 32 x D floats <= the two staged tiles
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+#pragma unroll
+    for (int md = 0; md < MD; ++md)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        f32x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = which ? dv[md][4 * g + e] : dk[md][4 * g + e];
+        *reinterpret_cast<f32x4*>(red + ((wave * 32 + l32) * D + md * 32 + g * 8 + hf * 4)) = w;
+      }
+    __syncthreads();
+    float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (khead * ((int64_t)a.nk << lg_th) + ((int64_t)j << lg_th)) * D;
+    const float mul = which ? 1.f : a.scale;
+    for (int x = tid; x < KH * 32 * (D / 4); x += 256) {
+      const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the block, group of four channels
+      if (kk >= th) continue;
+      const int g2 = kk / 32, k32 = kk % 32;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int r = 0; r < RH; ++r) acc += *reinterpret_cast<const f32x4*>(red + (((r * KH + g2) * 32 + k32) * D + c4 * 4));
+      *reinterpret_cast<f32x4*>(dst + (int64_t)kk * D + c4 * 4) = acc * mul;
+    }
+  }
+}
+
+size_t bwd_dkv_mfma_smem(int d) { return 2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float); }
+
+bool bwd_uses_mfma(const Plan& pl) {
+  return pl.dtype == PSA_BF16 && pl.bk >= 8 && pl.bk <= 128 && (pl.d == 64 || pl.d == 128);
+}
+
+template <int D, int KH>
+static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
+                               const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
+                               const bf16_t* go, float* dKp, float* dVp, int h, hipStream_t s) {
+  static LdsOptIn optin;
+  auto kern = bwd_dkv_mfma_kernel<D, KH>;
+  const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
+  if (e != hipSuccess) return e;
+  kern<<<dim3(pl.nk, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp,
+                                    const void* Vp, const uint8_t* M, const uint16_t* idx, const int32_t* cnt,
+                                    const float* lse, const void* dO, const float* Dr, float* dKp, float* dVp, void* dQ,
+                                    hipStream_t s) {
+  BwdMfmaArgs a;
+  a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
+  a.H = pl.H; a.causal = pl.causal; a.scale = pl.scale; a.scale_log2 = pl.scale * LOG2E;
+  a.lg_bk = 0;
+  while ((1 << a.lg_bk) < pl.bk) ++a.lg_bk;
+  int64_t off = 0;
+  for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) { a.lvl_off[h] = pl.lvl_off[h]; a.glvl_off[h] = 0; }
+  for (int h = 1; h <= pl.H; ++h) {
+    a.glvl_off[h] = off;
+    off += (int64_t)pl.B * pl.Hkv * pl.nk * (pl.bk >> (h - 1)) * pl.d;
+  }
+  const bf16_t* q = static_cast<const bf16_t*>(Q);
+  const bf16_t* k = static_cast<const bf16_t*>(K);
+  const bf16_t* v = static_cast<const bf16_t*>(V);
+  const bf16_t* kp = static_cast<const bf16_t*>(Kp);
+  const bf16_t* vp = static_cast<const bf16_t*>(Vp);
+  const bf16_t* go = static_cast<const bf16_t*>(dO);
+  const int slices = (pl.bq + 127) / 128;
+  bwd_dq_mfma_kernel<D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, 0, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
+                                                                           static_cast<bf16_t*>(dQ), a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  for (int h = 1; h <= pl.H; ++h) {
+    const int th = pl.bk >> (h - 1);
+    if (th > 64) e = launch_dkv_t<D, 4>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    else if (th > 32) e = launch_dkv_t<D, 2>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    else e = launch_dkv_t<D, 1>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// dQ and the pooled gradients dKp, dVp of every level (bfloat16 inputs); D = dO.O must be in Dr
+hipError_t launch_attn_bwd_mfma(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
+                                const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const float* lse, const void* dO,
+                                const float* Dr, float* dKp, float* dVp, void* dQ, hipStream_t s) {
+  return pl.d == 64 ? launch_bwd_mfma_t<64>(pl, Q, K, V, Kp, Vp, M, idx, cnt, lse, dO, Dr, dKp, dVp, dQ, s)
+                    : launch_bwd_mfma_t<128>(pl, Q, K, V, Kp, Vp, M, idx, cnt, lse, dO, Dr, dKp, dVp, dQ, s);
+}
+
+}  // namespace psa

@@ -91,6 +91,7 @@ hipError_t launch_attn_mfma(const Plan& pl, const void* Q, const void* K, const 
 size_t bwd_pooled_grad_elems(const Plan& pl);
 hipError_t launch_attn_bwd(const Plan& pl, const void* Q, const void* K, const void* V, const void* Kp, const void* Vp,
                            const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const void* O, const float* lse,
-                           const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, hipStream_t s);
+                           const void* dO, float* Dr, float* dKp, float* dVp, void* dQ, void* dK, void* dV, bool vector_unit,
+                           hipStream_t s);
 
 }  // namespace psa
