@@ -213,10 +213,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32, RH = 4 / KH;
   constexpr int TILEB = 128 * PITCH;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* Qs = smem;                       // [128][PITCH]
-  unsigned char* Gs = smem + TILEB;               // [128][PITCH]
-  float* lse_s = reinterpret_cast<float*>(smem + 2 * TILEB);   // [128], log2 domain, +inf for rows that do not exist
-  float* D_s = lse_s + 128;
+  // two buffers, each: Q rows [128][PITCH] | dO rows [128][PITCH] | lse [128] | D [128]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int kh = wave % KH, rh = wave / KH;
   const int j = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
@@ -252,71 +249,141 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dk[md][v] = 0.f; dv[md][v] = 0.f; }
 
-  for (int gq = 0; gq < group; ++gq) {
-    const int hq = hk * group + gq;
-    const int64_t qhead = (int64_t)b * a.Hq + hq;
-    const uint8_t* mcol = M + (qhead * a.nq) * a.nk + j;
-    for (int i = 0; i < a.nq; ++i) {
-      if ((int)mcol[(int64_t)i * a.nk] != h) continue;              // uniform over the workgroup
-      int row_end = (i + 1) * a.bq;
+  // The stages (a query head of the group, a query block that uses this key block at this level, 128
+  // of its rows) are walked with the NEXT stage's rows already on their way from memory into
+  // registers while the current one is multiplied; they go into the other LDS buffer afterwards.
+  constexpr int BUFB = 2 * TILEB + 2 * 128 * (int)sizeof(float);
+  // First the column of the level map: which (query head of the group, query block) pairs use this key
+  // block at this level, as an ordered list in LDS (one round of independent loads per 256 entries; a
+  // walk that tests one entry after the other spends a memory latency on each of them).
+  uint16_t* kept = reinterpret_cast<uint16_t*>(smem + 2 * BUFB);
+  const int E = group * a.nq;
+  int* wcount = reinterpret_cast<int*>(smem + 2 * BUFB + ((E * 2 + 15) & ~15));
+  int nkept = 0;
+  for (int e0 = 0; e0 < E; e0 += 256) {
+    const int e = e0 + tid;
+    bool hit = false;
+    if (e < E) {
+      const int64_t qhead = (int64_t)b * a.Hq + hk * group + e / a.nq;
+      hit = (int)M[(qhead * a.nq + e % a.nq) * a.nk + j] == h;
+    }
+    const uint64_t mask = __ballot(hit);
+    if (lane == 0) wcount[wave] = __popcll(mask);
+    __syncthreads();
+    int base = nkept;
+    for (int w = 0; w < wave; ++w) base += wcount[w];
+    if (hit) kept[base + __popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)e;
+    nkept += wcount[0] + wcount[1] + wcount[2] + wcount[3];
+    __syncthreads();
+  }
+  struct Stage { int k, gq, i, r0, seg; bool ok; };
+  auto settle = [&](Stage st) __attribute__((always_inline)) -> Stage {   // first existing stage at or after (k, r0)
+    for (; st.k < nkept; ++st.k, st.r0 = -1) {
+      const int e = (int)kept[st.k];
+      st.gq = e / a.nq;
+      st.i = e % a.nq;
+      int row_end = (st.i + 1) * a.bq;
       row_end = row_end < a.N ? row_end : a.N;
-      for (int r0 = i * a.bq; r0 < row_end; r0 += 128) {
-        const int seg = row_end - r0 < 128 ? row_end - r0 : 128;
-        __syncthreads();                           // the previous tile has been consumed
-#pragma unroll
-        for (int c = 0; c < 128 * CPR / 256; ++c) {
-          const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
-          u32x4 qv = {0u, 0u, 0u, 0u}, gv = {0u, 0u, 0u, 0u};
-          if (r < seg) {
-            qv = *reinterpret_cast<const u32x4*>(Q + (qhead * a.N + r0 + r) * D + ch * 8);
-            gv = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + r0 + r) * D + ch * 8);
-          }
-          *reinterpret_cast<u32x4*>(Qs + r * PITCH + ch * 16) = qv;
-          *reinterpret_cast<u32x4*>(Gs + r * PITCH + ch * 16) = gv;
-        }
-        if (tid < 128) {
-          lse_s[tid] = tid < seg ? lse[qhead * a.N + r0 + tid] * LOG2E : INFINITY;
-          D_s[tid] = tid < seg ? Dr[qhead * a.N + r0 + tid] : 0.f;
-        }
-        __syncthreads();
-        for (int c = rh; c * 32 < seg; c += RH) {  // this wavefront's 32-row chunks
-          f32x16 sc, dp;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) {
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
-          }
-          // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
-          float p[16], ds[16];
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            const int r = c * 32 + g4 * 8 + hf * 4;
-            const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
-            const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
-#pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-              float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias2) - ls[e4];
-              if (a.causal && last > r0 + r + e4) x = -INFINITY;
-              const float pv = __builtin_amdgcn_exp2f(x);
-              p[g4 * 4 + e4] = pv;
-              ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
-            }
-          }
-          bf16x8 pf[2], dsf[2];
-          pack_b(p, pf[0], pf[1]);
-          pack_b(ds, dsf[0], dsf[1]);
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int md = 0; md < MD; ++md) {
-              dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
-              dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
-            }
-        }
+      if (st.r0 < 0) st.r0 = st.i * a.bq;
+      if (st.r0 < row_end) {
+        st.seg = row_end - st.r0 < 128 ? row_end - st.r0 : 128;
+        st.ok = true;
+        return st;
       }
     }
+    st.ok = false;
+    return st;
+  };
+  constexpr int NCH = 128 * CPR / 256;             // 16-byte chunks per thread, tile and tensor
+  u32x4 qreg[NCH], greg[NCH];
+  float lreg = INFINITY, dreg = 0.f;
+  auto fetch = [&](const Stage& st) __attribute__((always_inline)) {
+    const int64_t qhead = (int64_t)b * a.Hq + hk * group + st.gq;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      qreg[c] = z;
+      greg[c] = z;
+      if (r < st.seg) {
+        qreg[c] = *reinterpret_cast<const u32x4*>(Q + (qhead * a.N + st.r0 + r) * D + ch * 8);
+        greg[c] = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + st.r0 + r) * D + ch * 8);
+      }
+    }
+    if (tid < 128) {
+      lreg = tid < st.seg ? lse[qhead * a.N + st.r0 + tid] * LOG2E : INFINITY;
+      dreg = tid < st.seg ? Dr[qhead * a.N + st.r0 + tid] : 0.f;
+    }
+  };
+  auto deposit = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* base = smem + buf * BUFB;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+      *reinterpret_cast<u32x4*>(base + r * PITCH + ch * 16) = qreg[c];
+      *reinterpret_cast<u32x4*>(base + TILEB + r * PITCH + ch * 16) = greg[c];
+    }
+    if (tid < 128) {
+      reinterpret_cast<float*>(base + 2 * TILEB)[tid] = lreg;
+      reinterpret_cast<float*>(base + 2 * TILEB)[128 + tid] = dreg;
+    }
+  };
+  Stage cur = settle(Stage{0, 0, 0, -1, 0, false});
+  if (cur.ok) {
+    fetch(cur);
+    deposit(0);
+  }
+  for (int buf = 0; cur.ok; buf ^= 1) {
+    Stage nxt = cur;
+    nxt.r0 += 128;
+    nxt = settle(nxt);
+    if (nxt.ok) fetch(nxt);
+    // this stage's rows are in LDS; the other buffer is no longer being read.  A bare barrier after the
+    // LDS counter alone: __syncthreads() would also wait for the loads just issued for the next stage.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const unsigned char* Qs = smem + buf * BUFB;
+    const unsigned char* Gs = Qs + TILEB;
+    const float* lse_s = reinterpret_cast<const float*>(Qs + 2 * TILEB);   // log2 domain, +inf for rows that do not exist
+    const float* D_s = lse_s + 128;
+    const int r0 = cur.r0, seg = cur.seg;
+    for (int c = rh; c * 32 < seg; c += RH) {  // this wavefront's 32-row chunks
+      f32x16 sc, dp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
+      }
+      // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
+      float p[16], ds[16];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int r = c * 32 + g4 * 8 + hf * 4;
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
+        const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias2) - ls[e4];
+          if (a.causal && last > r0 + r + e4) x = -INFINITY;
+          const float pv = __builtin_amdgcn_exp2f(x);
+          p[g4 * 4 + e4] = pv;
+          ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
+        }
+      }
+      bf16x8 pf[2], dsf[2];
+      pack_b(p, pf[0], pf[1]);
+      pack_b(ds, dsf[0], dsf[1]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int md = 0; md < MD; ++md) {
+          dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
+          dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
+        }
+    }
+    if (nxt.ok) deposit(buf ^ 1);
+    cur = nxt;
   }
   // partial sums of the wavefronts that share a key group -> LDS [wavefront][key][channel], added in a
   // fixed order; lane (key, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
@@ -347,10 +414,14 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   }
 }
 
-size_t bwd_dkv_mfma_smem(int d) { return 2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float); }
+// two staging buffers + the kept list of one column (entries: query heads per key head x query blocks) + 4 counters
+size_t bwd_dkv_mfma_smem(int d, int entries) {
+  return 2 * (2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float)) + (((size_t)entries * 2 + 15) & ~(size_t)15) + 16;
+}
 
 bool bwd_uses_mfma(const Plan& pl) {
-  return pl.dtype == PSA_BF16 && pl.bk >= 8 && pl.bk <= 128 && (pl.d == 64 || pl.d == 128);
+  return pl.dtype == PSA_BF16 && pl.bk >= 8 && pl.bk <= 128 && (pl.d == 64 || pl.d == 128) &&
+         (int64_t)pl.group * pl.nq <= 8192;      // the column's kept list sits in LDS next to the staging buffers
 }
 
 template <int D, int KH>
@@ -361,7 +432,7 @@ static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_
   auto kern = bwd_dkv_mfma_kernel<D, KH>;
   const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
-  kern<<<dim3(pl.nk, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
+  kern<<<dim3(pl.nk, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
   return hipGetLastError();
 }
 
