@@ -109,3 +109,30 @@ def test_hilbert_order_rejects_bad_grids(lib):
     assert lib.psa_hilbert_order(0, 4, 4, one) == 1
     assert lib.psa_hilbert_order(4, 4, 4, None) == 1
     assert lib.psa_hilbert_order(1 << 11, 1 << 11, 1 << 11, one) == 2
+
+
+def test_new_entry_points_validate_before_any_launch(lib):
+    """Null pointers, bad thresholds and bad reductions of the level cap, the permutation and the
+    backward pass are refused on the host (the pointers given are never dereferenced)."""
+    p = psa.make_params(1, 2, 2, 1024, 64, 64, 64, 4)
+    pp = ctypes.byref(p)
+    one = ctypes.c_void_p(256)
+    good = (ctypes.c_float * 3)(0.7, 0.65, 0.6)
+    bad = (ctypes.c_float * 3)(0.7, 1.5, 0.6)
+    assert lib.psa_level_cap(pp, one, good, 0, one, None, None) == 1            # no L
+    assert lib.psa_level_cap(pp, one, None, 0, one, one, None) == 1             # no thresholds
+    assert lib.psa_level_cap(pp, one, bad, 0, one, one, None) == 1              # threshold outside [-1, 1]
+    assert lib.psa_level_cap(pp, one, good, 7, one, one, None) == 1             # unknown reduction
+    assert lib.psa_level_cap(pp, None, good, 0, one, one, None) == 1            # no K
+    assert lib.psa_build_pyramid_cap(pp, one, one, one, None, good, 0, one, one, None) == 1
+    assert lib.psa_permute_tokens(pp, 2, one, one, 0, one, None) == 1           # X == Y
+    assert lib.psa_permute_tokens(pp, 0, one, one, 0, ctypes.c_void_p(512), None) == 1
+    assert lib.psa_permute_tokens(pp, 2, one, None, 0, ctypes.c_void_p(512), None) == 1
+    args = [one] * 13
+    assert lib.psa_attention_bwd(pp, *args[:7], None, *args[8:], None) == 1     # no lse
+    assert lib.psa_attention_bwd(pp, *args[:12], ctypes.c_void_p(264), None) == 1   # misaligned scratch
+    big = psa.make_params(1, 2, 2, 4096, 64, 256, 256, 2, sq=8, sk=8)
+    assert lib.psa_attention_bwd(ctypes.byref(big), *args, None) == 2            # b_k > 128
+    with pytest.raises(psa.PsaError):
+        psa.psa_query_bwd_sizes(big)
+    assert psa.psa_query_bwd_sizes(p) % 256 == 0

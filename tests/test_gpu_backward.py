@@ -105,3 +105,64 @@ def test_backward_is_reproducible_bit_for_bit():
         outs.append(g)
     for x, y in zip(*outs):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+def test_cap_permute_forward_backward_replay_from_a_captured_graph():
+    """Reordering, pyramid + similarity cap, allocation, attention, the inverse reordering and the
+    backward pass recorded into ONE HIP graph (none of them allocates, synchronises or records a memset
+    node) and replayed: every replay gives the eager results bit for bit, also after new inputs."""
+    import torch
+    w = si.small_variant(si.CONFIGS["dit1p3b"], 7 * 12 * 20, Hq=2, Hkv=2).with_(grid=(7, 12, 20))
+    gp = gpu_params(oracle_params(w))
+    Q, K, V = si.generate_qkv(w)
+    Qr, Kr, Vr = (to_dev(x, w.dtype) for x in (Q, K, V))
+    perm = torch.from_numpy(psa.psa_hilbert_order(*w.grid)).cuda()
+    Qd, Kd, Vd = (torch.empty_like(x) for x in (Qr, Kr, Vr))
+    buf = Buffers(gp)
+    sim = torch.empty((w.B, w.Hkv, gp.nk, w.levels - 1), dtype=torch.float32, device="cuda")
+    L = torch.empty((w.B, w.Hkv, gp.nk), dtype=torch.uint8, device="cuda")
+    Oout = torch.empty_like(buf.O)
+    dO = torch.randn_like(buf.O)
+    grads = [torch.empty_like(x) for x in (Qd, Kd, Vd)]
+    bscr = torch.empty(psa.psa_query_bwd_sizes(gp), dtype=torch.uint8, device="cuda")
+
+    def run():
+        for src, dst in ((Qr, Qd), (Kr, Kd), (Vr, Vd)):
+            psa.psa_permute_tokens(gp, src, perm, dst)
+        psa.psa_build_pyramid_cap(gp, Kd, Vd, buf.Kpyr, buf.Vpyr, (0.3, 0.2, 0.1), sim, L)
+        psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch, level_cap=L, rho_out=buf.rho)
+        psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch, lse=buf.lse)
+        psa.psa_permute_tokens(gp, buf.O, perm, Oout, inverse=True)
+        psa.psa_attention_bwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.lse, dO, *grads, bscr)
+
+    def snapshot():
+        return [t.clone() for t in (L, buf.M, Oout, *grads)]
+
+    def same(x, y):
+        return all(torch.equal(p.view(torch.uint8), q.view(torch.uint8)) for p, q in zip(x, y))
+
+    run()
+    torch.cuda.synchronize()
+    eager = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for it in range(3):
+        for t in (L, buf.M, Oout, *grads):
+            t.view(torch.uint8).fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert same(snapshot(), eager), it
+        float(Oout.float().sum().item())                 # eager work between the replays
+    Qr.copy_(torch.roll(Qr, 3, dims=2))
+    graph.replay()
+    torch.cuda.synchronize()
+    replayed = snapshot()
+    run()
+    torch.cuda.synchronize()
+    assert same(snapshot(), replayed) and not same(replayed, eager)
