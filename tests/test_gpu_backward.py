@@ -166,3 +166,41 @@ def test_cap_permute_forward_backward_replay_from_a_captured_graph():
     run()
     torch.cuda.synchronize()
     assert same(snapshot(), replayed) and not same(replayed, eager)
+
+
+@pytest.mark.parametrize("key,kv_heads", [("dit1p3b", (0, 11)), ("vlm_prefill", (3,))])
+def test_backward_full_size_workload(key, kv_heads):
+    """The benchmark configurations as stated: forward and backward run on the GPU for ALL heads; for the
+    listed key heads the oracle recomputes the gradients of the whole head (every query head of its group,
+    every query block) under the GPU's own level map."""
+    import torch
+    w = si.CONFIGS[key]
+    op = oracle_params(w)
+    gp = gpu_params(op)
+    Q, K, V = si.generate_qkv(w)
+    rng = np.random.default_rng(77)
+    dO = si.f32_to_bf16_bits(rng.standard_normal((w.B, w.Hq, w.N, w.d), dtype=np.float32))
+    Qd, Kd, Vd, dOd = (to_dev(x, w.dtype) for x in (Q, K, V, dO))
+    buf = Buffers(gp)
+    psa.psa_build_pyramid(gp, Kd, Vd, buf.Kpyr, buf.Vpyr)
+    psa.psa_allocate_levels(gp, Qd, Kd, buf.Kpyr, buf.M, buf.scratch)
+    psa.psa_attention_fwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.scratch, lse=buf.lse)
+    scratch = torch.empty(psa.psa_query_bwd_sizes(gp), dtype=torch.uint8, device="cuda")
+    dQ, dK, dV = (torch.full_like(x, float("nan")) for x in (Qd, Kd, Vd))
+    psa.psa_attention_bwd(gp, Qd, Kd, Vd, buf.Kpyr, buf.Vpyr, buf.M, buf.O, buf.lse, dOd, dQ, dK, dV, scratch)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dQ.view(-1)[::4099].float()).all()) and bool(torch.isfinite(dK.float()).all())
+    group = w.Hq // w.Hkv
+    for hk in kv_heads:
+        print(f"[full-size backward] {key}: oracle for key head {hk}", flush=True)
+        hq = slice(hk * group, (hk + 1) * group)
+        op1 = oracle_params(w, B=1, Hq=group, Hkv=1)
+        Q1, dO1 = si.to_f64(Q[:1, hq], w.dtype), si.to_f64(dO[:1, hq], w.dtype)
+        K1, V1 = si.to_f64(K[:1, hk:hk + 1], w.dtype), si.to_f64(V[:1, hk:hk + 1], w.dtype)
+        M1 = buf.M[:1, hq].cpu().numpy()
+        ref = orc.psa_attention_backward(Q1, orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1), M1, dO1, op1)
+        got = (from_dev(dQ[:1, hq], w.dtype), from_dev(dK[:1, hk:hk + 1], w.dtype), from_dev(dV[:1, hk:hk + 1], w.dtype))
+        for nm, g, want in zip(("dQ", "dK", "dV"), got, ref):
+            scale = max(float(np.abs(want).max()), 1.0)
+            assert np.abs(g - want).max() <= 2e-2 * scale, (nm, hk, np.abs(g - want).max(), scale)
+            assert rel_l2(g, want) <= 1e-2, (nm, hk, rel_l2(g, want))
