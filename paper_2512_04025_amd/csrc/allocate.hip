@@ -81,7 +81,7 @@ __device__ __forceinline__ uint64_t lane_xor64(uint64_t v, int m) {
 // instead of being read from memory.  That part is plain streaming work, so the workgroup then has
 // four wavefronts: all of them evaluate the row into LDS (and write it out if the caller wants the
 // scores); with NW = 1 three then retire and the first sorts the row.
-// NW = 4 (rows of more than 1024 blocks): the row is spread over the 256 lanes of four wavefronts,
+// NW = 4 (rows of more than 128 blocks): the row is spread over the 256 lanes of four wavefronts,
 // KPL keys each; the three merge steps whose partner lane sits in another wavefront go through LDS.
 // (One wavefront with 32 or 64 keys per lane needs 140+ registers: three wavefronts per SIMD, and the
 // sort, a chain of short dependent steps, then runs 6.8 times longer per row than with 16 keys per lane.)
@@ -319,9 +319,9 @@ hipError_t launch_allocate(const Plan& pl, const float* S, const FactoredScores*
   switch (kpl) {
     case 1:  return launch_alloc_t<1, 1>(pl, a, S, cap, M, rowcnt, s);
     case 2:  return launch_alloc_t<2, 1>(pl, a, S, cap, M, rowcnt, s);
-    case 4:  return launch_alloc_t<4, 1>(pl, a, S, cap, M, rowcnt, s);
-    case 8:  return launch_alloc_t<8, 1>(pl, a, S, cap, M, rowcnt, s);
-    case 16: return launch_alloc_t<16, 1>(pl, a, S, cap, M, rowcnt, s);
+    case 4:  return launch_alloc_t<1, 4>(pl, a, S, cap, M, rowcnt, s);    // from 256 keys on: four wavefronts per row
+    case 8:  return launch_alloc_t<2, 4>(pl, a, S, cap, M, rowcnt, s);    //   (5 us of 41 at 512 keys, 30 of 330 at 1024)
+    case 16: return launch_alloc_t<4, 4>(pl, a, S, cap, M, rowcnt, s);
     case 32: return launch_alloc_t<8, 4>(pl, a, S, cap, M, rowcnt, s);    // 2048 keys: 256 lanes x 8
     case 64: return launch_alloc_t<16, 4>(pl, a, S, cap, M, rowcnt, s);   // 4096 keys: 256 lanes x 16
     default: return hipErrorInvalidValue;   // more than PSA_MAX_NK key blocks: refused before any launch
