@@ -430,12 +430,22 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
         }
     }
     if (SWEEP == 1) {
+      float gmax[2][4];
       if (plain) {
         // the running maximum only moves when it would grow by more than 2^8: the common path is one
         // fused multiply-add, one exp2 and one add per logit
-        float bm = fmaxf(acc[0][0], acc[1][0]);
+        // the largest dot of every group of four keys once: the tile's maximum and the block maxima
+        // stored below both come from these (3-input maxima)
 #pragma unroll
-        for (int v = 1; v < 16; ++v) bm = __builtin_fmaxf(bm, __builtin_fmaxf(acc[0][v], acc[1][v]));   // v_max3
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            gmax[mb][g] = __builtin_fmaxf(__builtin_fmaxf(acc[mb][4 * g], __builtin_fmaxf(acc[mb][4 * g + 1], acc[mb][4 * g + 2])),
+                                          acc[mb][4 * g + 3]);
+        float bm = __builtin_fmaxf(gmax[0][0], __builtin_fmaxf(gmax[0][1], gmax[0][2]));
+        bm = __builtin_fmaxf(bm, __builtin_fmaxf(gmax[0][3], gmax[1][0]));
+        bm = __builtin_fmaxf(bm, __builtin_fmaxf(gmax[1][1], gmax[1][2]));
+        bm = __builtin_fmaxf(bm, gmax[1][3]);
         bm *= a.scale_log2;
         float p, q;
         both_halves(bm, p, q);
@@ -483,8 +493,8 @@ void importance_tiles_kernel(const bf16_t* __restrict__ Qrep,
         for (int g = 0; g < 4; ++g) {
           float r0, r1;
           if (plain) {
-            r0 = fmaxf(fmaxf(acc[0][4 * g], acc[0][4 * g + 1]), fmaxf(acc[0][4 * g + 2], acc[0][4 * g + 3])) * a.scale_log2;
-            r1 = fmaxf(fmaxf(acc[1][4 * g], acc[1][4 * g + 1]), fmaxf(acc[1][4 * g + 2], acc[1][4 * g + 3])) * a.scale_log2;
+            r0 = gmax[0][g] * a.scale_log2;
+            r1 = gmax[1][g] * a.scale_log2;
           } else {
             r0 = fmaxf(fmaxf(x[0][4 * g], x[0][4 * g + 1]), fmaxf(x[0][4 * g + 2], x[0][4 * g + 3]));
             r1 = fmaxf(fmaxf(x[1][4 * g], x[1][4 * g + 1]), fmaxf(x[1][4 * g + 2], x[1][4 * g + 3]));
