@@ -201,9 +201,12 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restri
   }
 }
 
-// KH: 32-key groups of the block at this level (1, 2 or 4); the 4 / KH wavefronts that share a key
-// group split the 32-row chunks of every staged query tile between them.
-template <int D, int KH>
+// One workgroup per (KH * 32 adjacent pooled keys, key head, level).  KH: 32-key tiles of the workgroup
+// (1, 2 or 4); the 4 / KH wavefronts that share a tile split the 32-row chunks of every staged query
+// tile between them.  Blocks of 32 pooled keys or more take KH = keys / 32 (one block per workgroup);
+// smaller blocks are packed G = KH * 32 / keys to a workgroup (at most 16), so that a 32-key matrix tile
+// is full and a query block is staged once for all the blocks of the group that it uses at this level.
+template <int D, int KH, bool CAUSAL>
 __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
                                                            const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M,
@@ -216,22 +219,29 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   // two buffers, each: Q rows [128][PITCH] | dO rows [128][PITCH] | lse [128] | D [128]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int kh = wave % KH, rh = wave / KH;
-  const int j = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
-  const int lg_th = a.lg_bk - (h - 1), th = 1 << lg_th, span = 1 << (h - 1);
+  const int hk = blockIdx.y, b = blockIdx.z;
+  const int lg_th = a.lg_bk - (h - 1), span = 1 << (h - 1);
+  int G = (KH * 32) >> lg_th;
+  G = G < 1 ? 1 : (G > 16 ? 16 : G);
+  const int j0 = blockIdx.x * G;
   const int group = a.Hq / a.Hkv;
   const int64_t khead = (int64_t)b * a.Hkv + hk;
   const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
   const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
 
-  // this lane's pooled key (B operands of both first products): key kh*32 + l32 of the block
+  // this lane's pooled key (B operands of both first products): key kh*32 + l32 of the group
   const int key = kh * 32 + l32;
-  const int prow = (j << lg_th) + key;
+  const int kblk = key >> lg_th;                  // its block within the group
+  const int prow = (j0 << lg_th) + key;
   const int first = prow * span;
   int ctok = a.N - first;
   ctok = ctok < 0 ? 0 : (ctok > span ? span : ctok);
-  const bool valid = key < th && ctok > 0;
+  const bool valid = kblk < G && j0 + kblk < a.nk && ctok > 0;
   const float bias2 = valid ? __log2f((float)ctok) : -INFINITY;
   const int last = first + (ctok > 0 ? ctok : 1) - 1;
+  // the blocks this wavefront's 32 keys belong to, as bits of a stage's block mask
+  const int wb0 = (kh * 32) >> lg_th, wb1 = (kh * 32 + 31) >> lg_th;
+  const uint32_t wave_bits = wb0 < G ? (((2u << (wb1 < G ? wb1 : G - 1)) - 1u) & ~((1u << wb0) - 1u)) : 0u;
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
@@ -243,43 +253,57 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     kf[ks] = __builtin_bit_cast(bf16x8, x);
     vf[ks] = __builtin_bit_cast(bf16x8, y);
   }
+  // The operands are declared used here, so that the wait for their loads stands here and not at their
+  // first use inside the stage loop, where it would also wait for the rows fetched ahead.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(kf[ks]), "v"(vf[ks]));
   f32x16 dk[MD], dv[MD];
 #pragma unroll
   for (int md = 0; md < MD; ++md)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dk[md][v] = 0.f; dv[md][v] = 0.f; }
 
-  // The stages (a query head of the group, a query block that uses this key block at this level, 128
-  // of its rows) are walked with the NEXT stage's rows already on their way from memory into
-  // registers while the current one is multiplied; they go into the other LDS buffer afterwards.
   constexpr int BUFB = 2 * TILEB + 2 * 128 * (int)sizeof(float);
-  // First the column of the level map: which (query head of the group, query block) pairs use this key
-  // block at this level, as an ordered list in LDS (one round of independent loads per 256 entries; a
-  // walk that tests one entry after the other spends a memory latency on each of them).
-  uint16_t* kept = reinterpret_cast<uint16_t*>(smem + 2 * BUFB);
+  // First the columns of the level map: which (query head of the group, query block) pairs use any of
+  // the group's key blocks at this level, as an ordered list in LDS with the blocks used as a bit mask
+  // (one round of independent loads per 256 entries; a walk that tests one entry after the other spends
+  // a memory latency on each of them).
   const int E = group * a.nq;
-  int* wcount = reinterpret_cast<int*>(smem + 2 * BUFB + ((E * 2 + 15) & ~15));
+  const int listb = (E * 2 + 15) & ~15;
+  uint16_t* kept = reinterpret_cast<uint16_t*>(smem + 2 * BUFB);
+  uint16_t* kmask = reinterpret_cast<uint16_t*>(smem + 2 * BUFB + listb);
+  int* wcount = reinterpret_cast<int*>(smem + 2 * BUFB + 2 * listb);
   int nkept = 0;
   for (int e0 = 0; e0 < E; e0 += 256) {
     const int e = e0 + tid;
-    bool hit = false;
+    uint32_t bits = 0u;
     if (e < E) {
       const int64_t qhead = (int64_t)b * a.Hq + hk * group + e / a.nq;
-      hit = (int)M[(qhead * a.nq + e % a.nq) * a.nk + j] == h;
+      const uint8_t* mrow = M + (qhead * a.nq + e % a.nq) * a.nk + j0;
+      for (int g = 0; g < G && j0 + g < a.nk; ++g) bits |= ((int)mrow[g] == h ? 1u : 0u) << g;
     }
+    const bool hit = bits != 0u;
     const uint64_t mask = __ballot(hit);
     if (lane == 0) wcount[wave] = __popcll(mask);
     __syncthreads();
     int base = nkept;
     for (int w = 0; w < wave; ++w) base += wcount[w];
-    if (hit) kept[base + __popcll(mask & ((1ull << lane) - 1ull))] = (uint16_t)e;
+    if (hit) {
+      const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+      kept[pos] = (uint16_t)e;
+      kmask[pos] = (uint16_t)bits;
+    }
     nkept += wcount[0] + wcount[1] + wcount[2] + wcount[3];
     __syncthreads();
   }
-  struct Stage { int k, gq, i, r0, seg; bool ok; };
+  // The stages (a pair on the list, 128 of the query block's rows) are walked with the NEXT stage's
+  // rows already on their way from memory into registers while the current one is multiplied; they go
+  // into the other LDS buffer afterwards.
+  struct Stage { int k, gq, i, r0, seg; uint32_t bits; bool ok; };
   auto settle = [&](Stage st) __attribute__((always_inline)) -> Stage {   // first existing stage at or after (k, r0)
     for (; st.k < nkept; ++st.k, st.r0 = -1) {
       const int e = (int)kept[st.k];
+      st.bits = kmask[st.k];
       st.gq = e / a.nq;
       st.i = e % a.nq;
       int row_end = (st.i + 1) * a.bq;
@@ -328,7 +352,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
       reinterpret_cast<float*>(base + 2 * TILEB)[128 + tid] = dreg;
     }
   };
-  Stage cur = settle(Stage{0, 0, 0, -1, 0, false});
+  Stage cur = settle(Stage{0, 0, 0, -1, 0, 0u, false});
   if (cur.ok) {
     fetch(cur);
     deposit(0);
@@ -346,47 +370,52 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     const float* lse_s = reinterpret_cast<const float*>(Qs + 2 * TILEB);   // log2 domain, +inf for rows that do not exist
     const float* D_s = lse_s + 128;
     const int r0 = cur.r0, seg = cur.seg;
-    for (int c = rh; c * 32 < seg; c += RH) {  // this wavefront's 32-row chunks
-      f32x16 sc, dp;
+    // this lane's key counts only if its block is used by this query block
+    const float bias_on = ((cur.bits >> kblk) & 1u) != 0u ? bias2 : -INFINITY;
+    if ((cur.bits & wave_bits) != 0u) {                                    // ... and so is one of this wavefront's
+      for (int c = rh; c * 32 < seg; c += RH) {                             // this wavefront's 32-row chunks
+        f32x16 sc, dp;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
-      }
-      // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
-      float p[16], ds[16];
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int r = c * 32 + g4 * 8 + hf * 4;
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
-        const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias2) - ls[e4];
-          if (a.causal && last > r0 + r + e4) x = -INFINITY;
-          const float pv = __builtin_amdgcn_exp2f(x);
-          p[g4 * 4 + e4] = pv;
-          ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
+        for (int ks = 0; ks < KS; ++ks) {
+          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
         }
-      }
-      bf16x8 pf[2], dsf[2];
-      pack_b(p, pf[0], pf[1]);
-      pack_b(ds, dsf[0], dsf[1]);
+        // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
+        float p[16], ds[16];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int r = c * 32 + g4 * 8 + hf * 4;
+          const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
+          const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
 #pragma unroll
-        for (int md = 0; md < MD; ++md) {
-          dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
-          dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
+          for (int e4 = 0; e4 < 4; ++e4) {
+            float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias_on) - ls[e4];
+            if (CAUSAL) x = last > r0 + r + e4 ? -INFINITY : x;
+            const float pv = __builtin_amdgcn_exp2f(x);
+            p[g4 * 4 + e4] = pv;
+            ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
+          }
         }
+        bf16x8 pf[2], dsf[2];
+        pack_b(p, pf[0], pf[1]);
+        pack_b(ds, dsf[0], dsf[1]);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int md = 0; md < MD; ++md) {
+            dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
+            dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
+          }
+      }
     }
     if (nxt.ok) deposit(buf ^ 1);
     cur = nxt;
   }
-  // partial sums of the wavefronts that share a key group -> LDS [wavefront][key][channel], added in a
-  // fixed order; lane (key, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4
+  // partial sums of the wavefronts that share a key tile -> LDS [wavefront][key][channel], added in a
+  // fixed order; lane (key, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4.  Every pooled key of the
+  // group is written (zeros where no query block used it).
   float* red = reinterpret_cast<float*>(smem);    // 4 x 32 x D floats <= the two staged tiles
   for (int which = 0; which < 2; ++which) {
     __syncthreads();
@@ -400,11 +429,12 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
         *reinterpret_cast<f32x4*>(red + ((wave * 32 + l32) * D + md * 32 + g * 8 + hf * 4)) = w;
       }
     __syncthreads();
-    float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (khead * ((int64_t)a.nk << lg_th) + ((int64_t)j << lg_th)) * D;
+    float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (khead * ((int64_t)a.nk << lg_th) + ((int64_t)j0 << lg_th)) * D;
     const float mul = which ? 1.f : a.scale;
     for (int x = tid; x < KH * 32 * (D / 4); x += 256) {
-      const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the block, group of four channels
-      if (kk >= th) continue;
+      const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the group, group of four channels
+      const int blk = kk >> lg_th;
+      if (blk >= G || j0 + blk >= a.nk) continue;
       const int g2 = kk / 32, k32 = kk % 32;
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -414,9 +444,10 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   }
 }
 
-// two staging buffers + the kept list of one column (entries: query heads per key head x query blocks) + 4 counters
+// two staging buffers + the kept list and block masks of the group's columns (entries: query heads per key
+// head x query blocks) + 4 counters
 size_t bwd_dkv_mfma_smem(int d, int entries) {
-  return 2 * (2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float)) + (((size_t)entries * 2 + 15) & ~(size_t)15) + 16;
+  return 2 * (2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 16;
 }
 
 bool bwd_uses_mfma(const Plan& pl) {
@@ -424,16 +455,32 @@ bool bwd_uses_mfma(const Plan& pl) {
          (int64_t)pl.group * pl.nq <= 8192;      // the column's kept list sits in LDS next to the staging buffers
 }
 
-template <int D, int KH>
+#ifndef PSA_BWD_SMALL_KH
+#define PSA_BWD_SMALL_KH 1
+#endif
+
+template <int D, int KH, bool CAUSAL>
 static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                                const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
                                const bf16_t* go, float* dKp, float* dVp, int h, hipStream_t s) {
   static LdsOptIn optin;
-  auto kern = bwd_dkv_mfma_kernel<D, KH>;
+  auto kern = bwd_dkv_mfma_kernel<D, KH, CAUSAL>;
   const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
-  kern<<<dim3(pl.nk, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, a);
+  const int th = pl.bk >> (h - 1);
+  int G = KH * 32 / th;                          // key blocks per workgroup, as in the kernel
+  G = G < 1 ? 1 : (G > 16 ? 16 : G);
+  kern<<<dim3((pl.nk + G - 1) / G, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
+                                                                                                  dKp, dVp, h, a);
   return hipGetLastError();
+}
+
+template <int D, int KH>
+static hipError_t launch_dkv_c(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
+                               const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
+                               const bf16_t* go, float* dKp, float* dVp, int h, hipStream_t s) {
+  return pl.causal ? launch_dkv_t<D, KH, true>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s)
+                   : launch_dkv_t<D, KH, false>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
 }
 
 template <int D>
@@ -465,9 +512,10 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
   if (e != hipSuccess) return e;
   for (int h = 1; h <= pl.H; ++h) {
     const int th = pl.bk >> (h - 1);
-    if (th > 64) e = launch_dkv_t<D, 4>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
-    else if (th > 32) e = launch_dkv_t<D, 2>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
-    else e = launch_dkv_t<D, 1>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    if (th > 64) e = launch_dkv_c<D, 4>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    else if (th > 32) e = launch_dkv_c<D, 2>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    else if (th == 32) e = launch_dkv_c<D, 1>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    else e = launch_dkv_c<D, PSA_BWD_SMALL_KH>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
