@@ -202,23 +202,36 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restri
 }
 
 // One workgroup per (KH * 32 adjacent pooled keys, key head, level).  KH: 32-key tiles of the workgroup
-// (1, 2 or 4); the 4 / KH wavefronts that share a tile split the 32-row chunks of every staged query
-// tile between them.  Blocks of 32 pooled keys or more take KH = keys / 32 (one block per workgroup);
-// smaller blocks are packed G = KH * 32 / keys to a workgroup (at most 16), so that a 32-key matrix tile
-// is full and a query block is staged once for all the blocks of the group that it uses at this level.
+// (1, 2 or 4).  Blocks of 32 pooled keys or more take KH = keys / 32 (one block per workgroup); smaller
+// blocks are packed G = KH * 32 / keys to a workgroup (at most 16), so that a 32-key matrix tile is full
+// and a query block is staged once for all the blocks of the group that it uses at this level.
+// Half of the wavefronts accumulate dKbar (they need S, dP and dS), the other half dVbar (S and P only):
+// that halves the accumulators a wavefront holds, so that two wavefronts fit on each SIMD (two
+// workgroups of four per compute unit, or one of eight for KH = 4) and the matrix pipe works for one
+// while the other is in its exponentials, its LDS reads or a barrier.  Wavefronts of the same half
+// that share a key tile (KH = 1: two of them) split the 32-row chunks of a staged tile.
+template <int D, int KH>
+struct DkvShape {
+  static constexpr int NW = KH == 4 ? 8 : 4, NT = NW * 64, RH = (NW / 2) / KH, ROWS = 64;
+  static constexpr int PITCH = D * 2 + 16, TILEB = ROWS * PITCH, BUFB = 2 * TILEB + 2 * ROWS * (int)sizeof(float);
+};
+
 template <int D, int KH, bool CAUSAL>
-__global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                           const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
-                                                           const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M,
-                                                           const float* __restrict__ lse, const float* __restrict__ Dr,
-                                                           const bf16_t* __restrict__ dO, float* __restrict__ dKp,
-                                                           float* __restrict__ dVp, int h, BwdMfmaArgs a) {
-  constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32, RH = 4 / KH;
-  constexpr int TILEB = 128 * PITCH;
+__global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
+    const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M, const float* __restrict__ lse, const float* __restrict__ Dr,
+    const bf16_t* __restrict__ dO, float* __restrict__ dKp, float* __restrict__ dVp, int h, BwdMfmaArgs a) {
+  using S = DkvShape<D, KH>;
+  constexpr int NW = S::NW, NT = S::NT, RH = S::RH, ROWS = S::ROWS, PITCH = S::PITCH, TILEB = S::TILEB, BUFB = S::BUFB;
+  constexpr int CPR = D / 8, KS = D / 16, MD = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // two buffers, each: Q rows [128][PITCH] | dO rows [128][PITCH] | lse [128] | D [128]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
-  const int kh = wave % KH, rh = wave / KH;
+  // two buffers, each: Q rows [ROWS][PITCH] | dO rows [ROWS][PITCH] | lse [ROWS] | D [ROWS]
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // 0: this wavefront accumulates dKbar, 1: dVbar.  The halves change places from one workgroup to the
+  // next, so that two workgroups on a compute unit do not put both heavier halves on the same SIMDs.
+  const int role = (wave / (NW / 2)) ^ (int)(blockIdx.x & 1);
+  const int w2 = wave % (NW / 2), kh = w2 % KH, rh = w2 / KH;
   const int hk = blockIdx.y, b = blockIdx.z;
   const int lg_th = a.lg_bk - (h - 1), span = 1 << (h - 1);
   int G = (KH * 32) >> lg_th;
@@ -242,13 +255,13 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   // the blocks this wavefront's 32 keys belong to, as bits of a stage's block mask
   const int wb0 = (kh * 32) >> lg_th, wb1 = (kh * 32 + 31) >> lg_th;
   const uint32_t wave_bits = wb0 < G ? (((2u << (wb1 < G ? wb1 : G - 1)) - 1u) & ~((1u << wb0) - 1u)) : 0u;
-  bf16x8 kf[KS], vf[KS];
+  bf16x8 kf[KS], vf[KS];                          // vf: only the dKbar half multiplies by it
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     u32x4 x = {0u, 0u, 0u, 0u}, y = {0u, 0u, 0u, 0u};
     if (valid) {
       x = *reinterpret_cast<const u32x4*>(kbase + (int64_t)prow * D + ks * 16 + hf * 8);
-      y = *reinterpret_cast<const u32x4*>(vbase + (int64_t)prow * D + ks * 16 + hf * 8);
+      if (role == 0) y = *reinterpret_cast<const u32x4*>(vbase + (int64_t)prow * D + ks * 16 + hf * 8);
     }
     kf[ks] = __builtin_bit_cast(bf16x8, x);
     vf[ks] = __builtin_bit_cast(bf16x8, y);
@@ -257,16 +270,15 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   // first use inside the stage loop, where it would also wait for the rows fetched ahead.
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(kf[ks]), "v"(vf[ks]));
-  f32x16 dk[MD], dv[MD];
+  f32x16 acc[MD];                                 // dKbar^T or dVbar^T of this lane's key
 #pragma unroll
   for (int md = 0; md < MD; ++md)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { dk[md][v] = 0.f; dv[md][v] = 0.f; }
+    for (int v = 0; v < 16; ++v) acc[md][v] = 0.f;
 
-  constexpr int BUFB = 2 * TILEB + 2 * 128 * (int)sizeof(float);
   // First the columns of the level map: which (query head of the group, query block) pairs use any of
   // the group's key blocks at this level, as an ordered list in LDS with the blocks used as a bit mask
-  // (one round of independent loads per 256 entries; a walk that tests one entry after the other spends
+  // (one round of independent loads per NT entries; a walk that tests one entry after the other spends
   // a memory latency on each of them).
   const int E = group * a.nq;
   const int listb = (E * 2 + 15) & ~15;
@@ -274,7 +286,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   uint16_t* kmask = reinterpret_cast<uint16_t*>(smem + 2 * BUFB + listb);
   int* wcount = reinterpret_cast<int*>(smem + 2 * BUFB + 2 * listb);
   int nkept = 0;
-  for (int e0 = 0; e0 < E; e0 += 256) {
+  for (int e0 = 0; e0 < E; e0 += NT) {
     const int e = e0 + tid;
     uint32_t bits = 0u;
     if (e < E) {
@@ -286,17 +298,21 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     const uint64_t mask = __ballot(hit);
     if (lane == 0) wcount[wave] = __popcll(mask);
     __syncthreads();
-    int base = nkept;
-    for (int w = 0; w < wave; ++w) base += wcount[w];
+    int base = nkept, total = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      base += w < wave ? wcount[w] : 0;
+      total += wcount[w];
+    }
     if (hit) {
       const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
       kept[pos] = (uint16_t)e;
       kmask[pos] = (uint16_t)bits;
     }
-    nkept += wcount[0] + wcount[1] + wcount[2] + wcount[3];
+    nkept += total;
     __syncthreads();
   }
-  // The stages (a pair on the list, 128 of the query block's rows) are walked with the NEXT stage's
+  // The stages (a pair on the list, ROWS of the query block's rows) are walked with the NEXT stage's
   // rows already on their way from memory into registers while the current one is multiplied; they go
   // into the other LDS buffer afterwards.
   struct Stage { int k, gq, i, r0, seg; uint32_t bits; bool ok; };
@@ -310,7 +326,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
       row_end = row_end < a.N ? row_end : a.N;
       if (st.r0 < 0) st.r0 = st.i * a.bq;
       if (st.r0 < row_end) {
-        st.seg = row_end - st.r0 < 128 ? row_end - st.r0 : 128;
+        st.seg = row_end - st.r0 < ROWS ? row_end - st.r0 : ROWS;
         st.ok = true;
         return st;
       }
@@ -318,14 +334,14 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     st.ok = false;
     return st;
   };
-  constexpr int NCH = 128 * CPR / 256;             // 16-byte chunks per thread, tile and tensor
+  constexpr int NCH = ROWS * CPR / NT;             // 16-byte chunks per thread, tile and tensor
   u32x4 qreg[NCH], greg[NCH];
   float lreg = INFINITY, dreg = 0.f;
   auto fetch = [&](const Stage& st) __attribute__((always_inline)) {
     const int64_t qhead = (int64_t)b * a.Hq + hk * group + st.gq;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+      const int x = tid + NT * c, r = x / CPR, ch = x % CPR;
       const u32x4 z = {0u, 0u, 0u, 0u};
       qreg[c] = z;
       greg[c] = z;
@@ -334,7 +350,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
         greg[c] = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + st.r0 + r) * D + ch * 8);
       }
     }
-    if (tid < 128) {
+    if (tid < ROWS) {
       lreg = tid < st.seg ? lse[qhead * a.N + st.r0 + tid] * LOG2E : INFINITY;
       dreg = tid < st.seg ? Dr[qhead * a.N + st.r0 + tid] : 0.f;
     }
@@ -343,13 +359,13 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     unsigned char* base = smem + buf * BUFB;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+      const int x = tid + NT * c, r = x / CPR, ch = x % CPR;
       *reinterpret_cast<u32x4*>(base + r * PITCH + ch * 16) = qreg[c];
       *reinterpret_cast<u32x4*>(base + TILEB + r * PITCH + ch * 16) = greg[c];
     }
-    if (tid < 128) {
+    if (tid < ROWS) {
       reinterpret_cast<float*>(base + 2 * TILEB)[tid] = lreg;
-      reinterpret_cast<float*>(base + 2 * TILEB)[128 + tid] = dreg;
+      reinterpret_cast<float*>(base + 2 * TILEB)[ROWS + tid] = dreg;
     }
   };
   Stage cur = settle(Stage{0, 0, 0, -1, 0, 0u, false});
@@ -359,7 +375,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
   }
   for (int buf = 0; cur.ok; buf ^= 1) {
     Stage nxt = cur;
-    nxt.r0 += 128;
+    nxt.r0 += ROWS;
     nxt = settle(nxt);
     if (nxt.ok) fetch(nxt);
     // this stage's rows are in LDS; the other buffer is no longer being read.  A bare barrier after the
@@ -368,86 +384,96 @@ __global__ __launch_bounds__(256) void bwd_dkv_mfma_kernel(const bf16_t* __restr
     const unsigned char* Qs = smem + buf * BUFB;
     const unsigned char* Gs = Qs + TILEB;
     const float* lse_s = reinterpret_cast<const float*>(Qs + 2 * TILEB);   // log2 domain, +inf for rows that do not exist
-    const float* D_s = lse_s + 128;
+    const float* D_s = lse_s + ROWS;
+    const unsigned char* Ts = role == 0 ? Qs : Gs;                         // dKbar^T += Q^T dS, dVbar^T += dO^T P
     const int r0 = cur.r0, seg = cur.seg;
     // this lane's key counts only if its block is used by this query block
     const float bias_on = ((cur.bits >> kblk) & 1u) != 0u ? bias2 : -INFINITY;
     if ((cur.bits & wave_bits) != 0u) {                                    // ... and so is one of this wavefront's
       for (int c = rh; c * 32 < seg; c += RH) {                             // this wavefront's 32-row chunks
-        f32x16 sc, dp;
+        f32x16 sc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+        for (int v = 0; v < 16; ++v) sc[v] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+        for (int ks = 0; ks < KS; ++ks)
           sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, PITCH, c * 32 + l32, ks * 16, hf), kf[ks], sc, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
-        }
         // this lane: key `key`, rows c*32 + (v/4)*8 + hf*4 + v%4
-        float p[16], ds[16];
+        float w[16];                               // P, or dS for the dKbar half
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
           const int r = c * 32 + g4 * 8 + hf * 4;
           const f32x4 ls = *reinterpret_cast<const f32x4*>(lse_s + r);
-          const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + r);
 #pragma unroll
           for (int e4 = 0; e4 < 4; ++e4) {
             float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, bias_on) - ls[e4];
             if (CAUSAL) x = last > r0 + r + e4 ? -INFINITY : x;
-            const float pv = __builtin_amdgcn_exp2f(x);
-            p[g4 * 4 + e4] = pv;
-            ds[g4 * 4 + e4] = pv * (dp[g4 * 4 + e4] - dd[e4]);
+            w[g4 * 4 + e4] = __builtin_amdgcn_exp2f(x);
           }
         }
-        bf16x8 pf[2], dsf[2];
-        pack_b(p, pf[0], pf[1]);
-        pack_b(ds, dsf[0], dsf[1]);
+        if (role == 0) {
+          f32x16 dp;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, PITCH, c * 32 + l32, ks * 16, hf), vf[ks], dp, 0, 0, 0);
+#pragma unroll
+          for (int g4 = 0; g4 < 4; ++g4) {
+            const f32x4 dd = *reinterpret_cast<const f32x4*>(D_s + c * 32 + g4 * 8 + hf * 4);
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) w[g4 * 4 + e4] *= dp[g4 * 4 + e4] - dd[e4];
+          }
+        }
+        bf16x8 wf[2];
+        pack_b(w, wf[0], wf[1]);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int md = 0; md < MD; ++md) {
-            dv[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Gs, PITCH, c * 32 + ks * 16, md * 32, lane), pf[ks], dv[md], 0, 0, 0);
-            dk[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Qs, PITCH, c * 32 + ks * 16, md * 32, lane), dsf[ks], dk[md], 0, 0, 0);
-          }
+          for (int md = 0; md < MD; ++md)
+            acc[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Ts, PITCH, c * 32 + ks * 16, md * 32, lane), wf[ks], acc[md], 0, 0, 0);
       }
     }
     if (nxt.ok) deposit(buf ^ 1);
     cur = nxt;
   }
-  // partial sums of the wavefronts that share a key tile -> LDS [wavefront][key][channel], added in a
-  // fixed order; lane (key, hf) holds channels md*32 + (v/4)*8 + hf*4 + v%4.  Every pooled key of the
-  // group is written (zeros where no query block used it).
-  float* red = reinterpret_cast<float*>(smem);    // 4 x 32 x D floats <= the two staged tiles
+  // partial sums of the wavefronts that share a key tile -> LDS [wavefront of the half][key][channel],
+  // added in a fixed order, first dKbar, then dVbar; lane (key, hf) holds channels
+  // md*32 + (v/4)*8 + hf*4 + v%4.  Every pooled key of the group is written (zeros where no query block
+  // used it).
+  float* red = reinterpret_cast<float*>(smem);    // NW/2 x 32 x D floats <= the two staged tiles
   for (int which = 0; which < 2; ++which) {
     __syncthreads();
+    if (role == which) {
 #pragma unroll
-    for (int md = 0; md < MD; ++md)
+      for (int md = 0; md < MD; ++md)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x4 w;
+        for (int g = 0; g < 4; ++g) {
+          f32x4 x;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = which ? dv[md][4 * g + e] : dk[md][4 * g + e];
-        *reinterpret_cast<f32x4*>(red + ((wave * 32 + l32) * D + md * 32 + g * 8 + hf * 4)) = w;
-      }
+          for (int e = 0; e < 4; ++e) x[e] = acc[md][4 * g + e];
+          *reinterpret_cast<f32x4*>(red + ((w2 * 32 + l32) * D + md * 32 + g * 8 + hf * 4)) = x;
+        }
+    }
     __syncthreads();
     float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (khead * ((int64_t)a.nk << lg_th) + ((int64_t)j0 << lg_th)) * D;
     const float mul = which ? 1.f : a.scale;
-    for (int x = tid; x < KH * 32 * (D / 4); x += 256) {
+    for (int x = tid; x < KH * 32 * (D / 4); x += NT) {
       const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the group, group of four channels
       const int blk = kk >> lg_th;
       if (blk >= G || j0 + blk >= a.nk) continue;
       const int g2 = kk / 32, k32 = kk % 32;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int r = 0; r < RH; ++r) acc += *reinterpret_cast<const f32x4*>(red + (((r * KH + g2) * 32 + k32) * D + c4 * 4));
-      *reinterpret_cast<f32x4*>(dst + (int64_t)kk * D + c4 * 4) = acc * mul;
+      for (int r = 0; r < RH; ++r) sum += *reinterpret_cast<const f32x4*>(red + (((r * KH + g2) * 32 + k32) * D + c4 * 4));
+      *reinterpret_cast<f32x4*>(dst + (int64_t)kk * D + c4 * 4) = sum * mul;
     }
   }
 }
 
 // two staging buffers + the kept list and block masks of the group's columns (entries: query heads per key
-// head x query blocks) + 4 counters
+// head x query blocks) + 8 counters
 size_t bwd_dkv_mfma_smem(int d, int entries) {
-  return 2 * (2 * (size_t)128 * (d * 2 + 16) + 2 * 128 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 16;
+  return 2 * (2 * (size_t)64 * (d * 2 + 16) + 2 * 64 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 32;
 }
 
 bool bwd_uses_mfma(const Plan& pl) {
@@ -470,7 +496,7 @@ static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_
   const int th = pl.bk >> (h - 1);
   int G = KH * 32 / th;                          // key blocks per workgroup, as in the kernel
   G = G < 1 ? 1 : (G > 16 ? 16 : G);
-  kern<<<dim3((pl.nk + G - 1) / G, pl.Hkv, pl.B), 256, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
+  kern<<<dim3((pl.nk + G - 1) / G, pl.Hkv, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
                                                                                                   dKp, dVp, h, a);
   return hipGetLastError();
 }
