@@ -68,17 +68,16 @@ __device__ __forceinline__ void pack_b(const float (&x)[16], bf16x8& f0, bf16x8&
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                          const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
-                                                          const bf16_t* __restrict__ Vp, const uint16_t* __restrict__ idx,
-                                                          const int32_t* __restrict__ cnt, const float* __restrict__ lse,
-                                                          const float* __restrict__ Dr, const bf16_t* __restrict__ dO,
-                                                          bf16_t* __restrict__ dQ, BwdMfmaArgs a) {
+__global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                             const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
+                                                             const bf16_t* __restrict__ Vp, const uint16_t* __restrict__ idx,
+                                                             const int32_t* __restrict__ cnt, const float* __restrict__ lse,
+                                                             const float* __restrict__ Dr, const bf16_t* __restrict__ dO,
+                                                             bf16_t* __restrict__ dQ, BwdMfmaArgs a) {
   constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[64 * PITCH];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[64 * PITCH];
-  __shared__ float term_s[64];
-  __shared__ int last_s[64];
+  constexpr int TILEB = 64 * PITCH, BUFB = 2 * TILEB + 2 * 64 * 4;
+  // two buffers, each: Kbar rows [64][PITCH] | Vbar rows [64][PITCH] | bias term [64] | last token [64]
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int slices = (a.bq + 127) / 128;
   const int i = blockIdx.x / slices, slice = blockIdx.x % slices;
@@ -101,8 +100,13 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restri
     qf[ks] = __builtin_bit_cast(bf16x8, x);
     gf[ks] = __builtin_bit_cast(bf16x8, y);
   }
-  const float lse2 = active ? lse[qhead * a.N + qrow] * LOG2E : INFINITY;   // inactive rows: every weight 0
-  const float my_D = active ? Dr[qhead * a.N + qrow] : 0.f;
+  float lse2 = active ? lse[qhead * a.N + qrow] * LOG2E : INFINITY;   // inactive rows: every weight 0
+  float my_D = active ? Dr[qhead * a.N + qrow] : 0.f;
+  // The wait for these loads stands here and not at their first use inside the tile loop, where it would
+  // also wait for the rows fetched ahead.
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" ::"v"(qf[ks]), "v"(gf[ks]));
+  asm volatile("" : "+v"(lse2), "+v"(my_D));
   f32x16 dq[MD];
 #pragma unroll
   for (int md = 0; md < MD; ++md)
@@ -112,80 +116,146 @@ __global__ __launch_bounds__(256) void bwd_dq_mfma_kernel(const bf16_t* __restri
   const int64_t srow = qhead * a.nq + i;
   const uint16_t* my_idx = idx + srow * a.nk;
   const int32_t* my_cnt = cnt + srow * CNT_STRIDE;
-  int lvl_start = 0;
-  for (int h = 1; h <= a.H; ++h) {
-    const int nblk = my_cnt[h - 1];
-    const int lg_th = a.lg_bk - (h - 1), th = 1 << lg_th, span = 1 << (h - 1);
-    const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
-    const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
-    const int ntl = ((nblk << lg_th) + 63) >> 6;
-    for (int tl = 0; tl < ntl; ++tl) {
-      __syncthreads();                           // the previous tile has been consumed
-      // gather the tile: row r of the tile is pooled row (block id << lg_th) | (stream position & (th-1))
-#pragma unroll
-      for (int c = 0; c < 64 * CPR / 256; ++c) {
-        const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
-        const int g = (tl << 6) + r, e = g >> lg_th;
-        u32x4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-        if (e < nblk) {
-          const int prow = ((int)my_idx[lvl_start + e] << lg_th) | (g & (th - 1));
-          if (prow * span < a.N) {
-            kv = *reinterpret_cast<const u32x4*>(kbase + (int64_t)prow * D + ch * 8);
-            vv = *reinterpret_cast<const u32x4*>(vbase + (int64_t)prow * D + ch * 8);
-          }
-        }
-        *reinterpret_cast<u32x4*>(Ks + r * PITCH + ch * 16) = kv;
-        *reinterpret_cast<u32x4*>(Vs + r * PITCH + ch * 16) = vv;
+
+  // The tiles of 64 pooled keys, level after level down the row's level-sorted block list.  Three are in
+  // flight: one is multiplied from LDS, the rows of the next are on their way from memory into
+  // registers (they go into the other LDS buffer afterwards), and the block ids that say where the rows
+  // of the one after that lie are being read.
+  struct Tile { int h, tl, ntl, nblk, start; bool ok; };
+  auto settle = [&](Tile t) __attribute__((always_inline)) -> Tile {   // first existing tile at or after (h, tl)
+    for (; t.h <= a.H; ++t.h, t.tl = 0, t.start += t.nblk, t.ntl = -1) {
+      if (t.ntl < 0) {
+        t.nblk = my_cnt[t.h - 1];
+        t.ntl = ((t.nblk << (a.lg_bk - (t.h - 1))) + 63) >> 6;
       }
-      if (tid < 64) {
-        const int g = (tl << 6) + tid, e = g >> lg_th;
-        float term = -INFINITY;
-        int last = 0;
-        if (e < nblk) {
-          const int prow = ((int)my_idx[lvl_start + e] << lg_th) | (g & (th - 1));
-          const int first = prow * span;
-          int c = a.N - first;
-          c = c < 0 ? 0 : (c > span ? span : c);
-          if (c > 0) term = __log2f((float)c);
-          last = first + (c > 0 ? c : 1) - 1;
-        }
-        term_s[tid] = term;
-        last_s[tid] = last;
+      if (t.tl < t.ntl) {
+        t.ok = true;
+        return t;
       }
-      __syncthreads();
-      bf16x8 dsf[4];
+    }
+    t.ok = false;
+    return t;
+  };
+  constexpr int NCH = 64 * CPR / 256;              // 16-byte chunks per thread, tile and tensor
+  struct Where { int prow[NCH], mine; };            // pooled rows of this thread's chunks and of tile row `tid`; -1: none
+  auto locate = [&](const Tile& t) __attribute__((always_inline)) -> Where {
+    Where w;
+    const int lg_th = a.lg_bk - (t.h - 1), th = 1 << lg_th;
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        f32x16 sc, dp;
+    for (int c = 0; c < NCH; ++c) {
+      const int r = (tid + 256 * c) / CPR, g = (t.tl << 6) + r, e = g >> lg_th;
+      w.prow[c] = e < t.nblk ? ((int)my_idx[t.start + e] << lg_th) | (g & (th - 1)) : -1;
+    }
+    w.mine = -1;
+    if (tid < 64) {
+      const int g = (t.tl << 6) + tid, e = g >> lg_th;
+      if (e < t.nblk) w.mine = ((int)my_idx[t.start + e] << lg_th) | (g & (th - 1));
+    }
+    return w;
+  };
+  u32x4 kreg[NCH], vreg[NCH];
+  float treg = -INFINITY;
+  int lastreg = 0;
+  auto fetch = [&](const Tile& t, const Where& w) __attribute__((always_inline)) {
+    const int lg_th = a.lg_bk - (t.h - 1), span = 1 << (t.h - 1);
+    const bf16_t* kbase = t.h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[t.h] + khead * ((int64_t)a.nk << lg_th) * D;
+    const bf16_t* vbase = t.h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[t.h] + khead * ((int64_t)a.nk << lg_th) * D;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, PITCH, mb * 32 + l32, ks * 16, hf), qf[ks], sc, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, PITCH, mb * 32 + l32, ks * 16, hf), gf[ks], dp, 0, 0, 0);
-        }
-        float ds[16];
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          const int col = mb * 32 + g4 * 8 + hf * 4;
-          const f32x4 tm = *reinterpret_cast<const f32x4*>(term_s + col);
-#pragma unroll
-          for (int e4 = 0; e4 < 4; ++e4) {
-            float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, tm[e4]) - lse2;
-            if (a.causal && last_s[col + e4] > qrow) x = -INFINITY;
-            const float p = __builtin_amdgcn_exp2f(x);
-            ds[g4 * 4 + e4] = p * (dp[g4 * 4 + e4] - my_D);
-          }
-        }
-        pack_b(ds, dsf[2 * mb], dsf[2 * mb + 1]);
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = (tid + 256 * c) % CPR;
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      kreg[c] = z;
+      vreg[c] = z;
+      if (w.prow[c] >= 0 && w.prow[c] * span < a.N) {
+        kreg[c] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)w.prow[c] * D + ch * 8);
+        vreg[c] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)w.prow[c] * D + ch * 8);
       }
+    }
+    treg = -INFINITY;
+    lastreg = 0;
+    if (w.mine >= 0) {
+      const int first = w.mine * span;
+      int c = a.N - first;
+      c = c < 0 ? 0 : (c > span ? span : c);
+      if (c > 0) treg = __log2f((float)c);
+      lastreg = first + (c > 0 ? c : 1) - 1;
+    }
+  };
+  auto deposit = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* base = smem + buf * BUFB;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
+    for (int c = 0; c < NCH; ++c) {
+      const int x = tid + 256 * c, r = x / CPR, ch = x % CPR;
+      *reinterpret_cast<u32x4*>(base + r * PITCH + ch * 16) = kreg[c];
+      *reinterpret_cast<u32x4*>(base + TILEB + r * PITCH + ch * 16) = vreg[c];
+    }
+    if (tid < 64) {
+      reinterpret_cast<float*>(base + 2 * TILEB)[tid] = treg;
+      reinterpret_cast<int*>(base + 2 * TILEB)[64 + tid] = lastreg;
+    }
+  };
+  Tile cur = settle(Tile{1, 0, -1, 0, 0, false});
+  Tile nxt = cur, nn = cur;
+  Where wn = {}, wnn = {};
+  if (cur.ok) {
+    fetch(cur, locate(cur));
+    deposit(0);
+    nxt.tl += 1;
+    nxt = settle(nxt);
+    if (nxt.ok) wn = locate(nxt);
+  }
+  for (int buf = 0; cur.ok; buf ^= 1) {
+    if (nxt.ok) {
+      nn = nxt;
+      nn.tl += 1;
+      nn = settle(nn);
+      if (nn.ok) wnn = locate(nn);
+      fetch(nxt, wn);
+    } else {
+      nn.ok = false;
+    }
+    // this tile's rows are in LDS; the other buffer is no longer being read.  A bare barrier after the
+    // LDS counter alone: __syncthreads() would also wait for the loads just issued for the next tiles.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    const unsigned char* Ks = smem + buf * BUFB;
+    const unsigned char* Vs = Ks + TILEB;
+    const float* term_s = reinterpret_cast<const float*>(Ks + 2 * TILEB);
+    const int* last_s = reinterpret_cast<const int*>(Ks + 2 * TILEB) + 64;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      f32x16 sc, dp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, PITCH, mb * 32 + l32, ks * 16, hf), qf[ks], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, PITCH, mb * 32 + l32, ks * 16, hf), gf[ks], dp, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int col = mb * 32 + g4 * 8 + hf * 4;
+        const f32x4 tm = *reinterpret_cast<const f32x4*>(term_s + col);
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          float x = fmaf(sc[g4 * 4 + e4], a.scale_log2, tm[e4]) - lse2;
+          if (a.causal) x = last_s[col + e4] > qrow ? -INFINITY : x;
+          const float p = __builtin_amdgcn_exp2f(x);
+          ds[g4 * 4 + e4] = p * (dp[g4 * 4 + e4] - my_D);
+        }
+      }
+      bf16x8 dsf[2];
+      pack_b(ds, dsf[0], dsf[1]);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int md = 0; md < MD; ++md)
-          dq[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Ks, PITCH, ks * 16, md * 32, lane), dsf[ks], dq[md], 0, 0, 0);
+          dq[md] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(Ks, PITCH, mb * 32 + ks * 16, md * 32, lane), dsf[ks], dq[md], 0, 0, 0);
     }
-    lvl_start += nblk;
+    if (nxt.ok) deposit(buf ^ 1);
+    cur = nxt;
+    nxt = nn;
+    wn = wnn;
   }
   if (active) {
     bf16_t* op = dQ + (qhead * a.N + qrow) * D;
@@ -532,9 +602,13 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
   const bf16_t* vp = static_cast<const bf16_t*>(Vp);
   const bf16_t* go = static_cast<const bf16_t*>(dO);
   const int slices = (pl.bq + 127) / 128;
-  bwd_dq_mfma_kernel<D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, 0, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
-                                                                           static_cast<bf16_t*>(dQ), a);
-  hipError_t e = hipGetLastError();
+  static LdsOptIn dq_optin;
+  hipError_t e = allow_max_lds(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>), &dq_optin);
+  if (e != hipSuccess) return e;
+  constexpr size_t dq_smem = 2 * (2 * (size_t)64 * (D * 2 + 16) + 2 * 64 * 4);   // two buffers of the kernel's layout
+  bwd_dq_mfma_kernel<D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, dq_smem, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
+                                                                                 static_cast<bf16_t*>(dQ), a);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   for (int h = 1; h <= pl.H; ++h) {
     const int th = pl.bk >> (h - 1);
