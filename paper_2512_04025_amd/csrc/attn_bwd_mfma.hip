@@ -3,20 +3,21 @@
 // vector-unit version that serves float32 and the shapes this one does not take).
 //
 // Two kernels, both on 32x32x16 MFMAs with fp32 accumulation, P and dS rounded to bfloat16 for the
-// products that consume them, no atomics:
+// products that consume them, no atomics, two wavefronts per SIMD (at most 256 registers per lane),
+// tiles double-buffered through registers into LDS:
 //   bwd_dq_mfma_kernel   one workgroup per 128 query rows (a wavefront per 32), walking the row's
 //        level-sorted block list in tiles of 64 pooled keys gathered into LDS.  Same operand roles as the
 //        forward kernel: S^T = Kbar Q^T and dP^T = Vbar dO^T put one query row in each lane (lse and
 //        D = dO.O are per-lane scalars), dS^T is packed in registers as the B operand of
 //        dQ^T += Kbar^T dS^T, whose A operand is read from the row-major Kbar tile with the transposing
 //        LDS load.
-//   bwd_dkv_mfma_kernel  the same with queries and keys exchanged: one workgroup per (key block, key
-//        head, level); the block's pooled keys and values sit in registers as B operands (one key per
-//        lane), the query blocks that use this block at this level (a walk down the level map's
-//        column, for every query head of the group) are staged through LDS 128 rows at a time;
-//        S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and dKbar^T += Q^T dS with the
-//        transposing load on the staged dO and Q.  The four wavefronts split the key halves and the
-//        row chunks between them and add their partial sums through LDS at the end.
+//   bwd_dkv_mfma_kernel  the same with queries and keys exchanged: one workgroup per (32, 64 or 128
+//        adjacent pooled keys of a level, key head); the pooled keys and values sit in registers as B
+//        operands (one key per lane), the query blocks that use one of the workgroup's key blocks at this
+//        level (a walk down the level map's columns, for every query head of the group) are staged
+//        through LDS 64 rows at a time; S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and
+//        dKbar^T += Q^T dS with the transposing load on the staged dO and Q.  Half of the wavefronts
+//        accumulate dKbar, the other half dVbar.
 // LDS rows carry 16 bytes of padding, which spreads the rows of an operand read over all banks.
 #include "psa_dev.h"
 #include "psa_internal.h"
