@@ -168,11 +168,12 @@ def test_cap_permute_forward_backward_replay_from_a_captured_graph():
     assert same(snapshot(), replayed) and not same(replayed, eager)
 
 
-@pytest.mark.parametrize("key,kv_heads", [("dit1p3b", (0, 11)), ("vlm_prefill", (3,))])
-def test_backward_full_size_workload(key, kv_heads):
+@pytest.mark.parametrize("key,bi,kv_heads", [("dit1p3b", 0, (0, 11)), ("vlm_prefill", 0, (3,)), ("dit14b", 0, (39,)),
+                                             ("stress", 1, (15,))])
+def test_backward_full_size_workload(key, bi, kv_heads):
     """The benchmark configurations as stated: forward and backward run on the GPU for ALL heads; for the
-    listed key heads the oracle recomputes the gradients of the whole head (every query head of its group,
-    every query block) under the GPU's own level map."""
+    listed key heads of batch entry `bi` the oracle recomputes the gradients of the whole head (every query
+    head of its group, every query block) under the GPU's own level map."""
     import torch
     w = si.CONFIGS[key]
     op = oracle_params(w)
@@ -195,11 +196,12 @@ def test_backward_full_size_workload(key, kv_heads):
         print(f"[full-size backward] {key}: oracle for key head {hk}", flush=True)
         hq = slice(hk * group, (hk + 1) * group)
         op1 = oracle_params(w, B=1, Hq=group, Hkv=1)
-        Q1, dO1 = si.to_f64(Q[:1, hq], w.dtype), si.to_f64(dO[:1, hq], w.dtype)
-        K1, V1 = si.to_f64(K[:1, hk:hk + 1], w.dtype), si.to_f64(V[:1, hk:hk + 1], w.dtype)
-        M1 = buf.M[:1, hq].cpu().numpy()
+        bs = slice(bi, bi + 1)
+        Q1, dO1 = si.to_f64(Q[bs, hq], w.dtype), si.to_f64(dO[bs, hq], w.dtype)
+        K1, V1 = si.to_f64(K[bs, hk:hk + 1], w.dtype), si.to_f64(V[bs, hk:hk + 1], w.dtype)
+        M1 = buf.M[bs, hq].cpu().numpy()
         ref = orc.psa_attention_backward(Q1, orc.build_pyramid(K1, op1), orc.build_pyramid(V1, op1), M1, dO1, op1)
-        got = (from_dev(dQ[:1, hq], w.dtype), from_dev(dK[:1, hk:hk + 1], w.dtype), from_dev(dV[:1, hk:hk + 1], w.dtype))
+        got = (from_dev(dQ[bs, hq], w.dtype), from_dev(dK[bs, hk:hk + 1], w.dtype), from_dev(dV[bs, hk:hk + 1], w.dtype))
         for nm, g, want in zip(("dQ", "dK", "dV"), got, ref):
             scale = max(float(np.abs(want).max()), 1.0)
             assert np.abs(g - want).max() <= 2e-2 * scale, (nm, hk, np.abs(g - want).max(), scale)
