@@ -38,16 +38,26 @@ __device__ __forceinline__ float quad_sum(float x) {
 // round-robin to the four lanes of a quad, so a quad reads 16 consecutive floats of an LDS row at once
 __device__ __forceinline__ int quad_channel(int e, int qd) { return (e >> 2) * 16 + qd * 4 + (e & 3); }
 
+// out[r] = A[r] . B[r] (D = dO . O of the softmax backward).  A row is shared by d / VEC consecutive lanes
+// (8, 16 or 32), each with one 16-byte load per tensor; the partial sums meet in a butterfly.
 template <typename T>
 __global__ __launch_bounds__(256) void rowdot_kernel(const T* __restrict__ A, const T* __restrict__ Bm,
                                                      float* __restrict__ out, int64_t rows, int d) {
-  const int64_t r = (int64_t)blockIdx.x * 64 + (threadIdx.x >> 2);
-  const int qd = threadIdx.x & 3;
+  constexpr int VEC = Elem<T>::VEC;
+  const int lpr = d / VEC;                         // lanes per row: a power of two that divides 64
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t r = gid / lpr;
+  const int c = (int)(gid % lpr) * VEC;
   float acc = 0.f;
-  if (r < rows)
-    for (int c = qd; c < d; c += 4) acc = fmaf(Elem<T>::to_f32(A[r * d + c]), Elem<T>::to_f32(Bm[r * d + c]), acc);
-  acc = quad_sum(acc);
-  if (r < rows && qd == 0) out[r] = acc;
+  if (r < rows) {
+    float x[VEC], y[VEC];
+    Elem<T>::load(A + r * d + c, x);
+    Elem<T>::load(Bm + r * d + c, y);
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) acc = fmaf(x[u], y[u], acc);
+  }
+  for (int o = 1; o < lpr; o <<= 1) acc += __shfl_xor(acc, o, 64);
+  if (r < rows && c == 0) out[r] = acc;
 }
 
 // Stage `seg` pooled rows [prow0, prow0 + seg) of level h (K and V of one key head) into LDS as fp32,
@@ -264,9 +274,12 @@ __global__ __launch_bounds__(512) void bwd_dkv_kernel(const T* __restrict__ Q, c
 }
 
 // dK[t] = sum_h dKbar^h[t >> (h-1)] / c  (Eq. 2-3 backwards); same for V.  One thread per 4 channels.
+// The pooled gradients of a key head come in `parts` consecutive partial tensors (one per query head of
+// its group when the matrix-core kernel wrote them), added here in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void unpool_kernel(const float* __restrict__ dKp, const float* __restrict__ dVp,
-                                                     T* __restrict__ dK, T* __restrict__ dV, int heads, int d, BwdArgs a) {
+                                                     T* __restrict__ dK, T* __restrict__ dV, int heads, int parts, int d,
+                                                     BwdArgs a) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int q4 = d / 4;
   if (gid >= (int64_t)heads * a.N * q4) return;
@@ -281,7 +294,9 @@ __global__ __launch_bounds__(256) void unpool_kernel(const float* __restrict__ d
     const int prow = t >> (h - 1);
     int c = a.N - prow * span;
     c = c > span ? span : c;                       // >= 1: token t is under this pooled token
-    const f32x4 g = *reinterpret_cast<const f32x4*>(src + a.glvl_off[h] + (bh * (int64_t)a.nk * th + prow) * d + c4 * 4);
+    f32x4 g = {0.f, 0.f, 0.f, 0.f};
+    for (int part = 0; part < parts; ++part)
+      g += *reinterpret_cast<const f32x4*>(src + a.glvl_off[h] + ((bh * parts + part) * (int64_t)a.nk * th + prow) * d + c4 * 4);
     const float inv = 1.f / (float)c;
     acc += g * inv;
   }
@@ -295,9 +310,12 @@ hipError_t launch_attn_bwd_mfma(const Plan& pl, const void* Q, const void* K, co
                                 const uint8_t* M, const uint16_t* idx, const int32_t* cnt, const float* lse, const void* dO,
                                 const float* Dr, float* dKp, float* dVp, void* dQ, hipStream_t s);
 
-size_t bwd_pooled_grad_elems(const Plan& pl) {      // one tensor: levels 1..H
+// partial pooled-gradient tensors per key head: the matrix-core kernel writes one per query head of the group
+int bwd_parts(const Plan& pl) { return bwd_uses_mfma(pl) ? pl.group : 1; }
+
+size_t bwd_pooled_grad_elems(const Plan& pl) {      // one tensor: levels 1..H, every part
   size_t n = 0;
-  for (int h = 1; h <= pl.H; ++h) n += (size_t)pl.B * pl.Hkv * pl.nk * (pl.bk >> (h - 1)) * pl.d;
+  for (int h = 1; h <= pl.H; ++h) n += (size_t)pl.B * pl.Hkv * bwd_parts(pl) * pl.nk * (pl.bk >> (h - 1)) * pl.d;
   return n;
 }
 
@@ -309,11 +327,12 @@ static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, con
   BwdArgs a;
   a.N = pl.N; a.Hq = pl.Hq; a.Hkv = pl.Hkv; a.nq = pl.nq; a.nk = pl.nk; a.bq = pl.bq; a.bk = pl.bk;
   a.H = pl.H; a.causal = pl.causal; a.scale = pl.scale;
+  const int parts = use_mfma ? pl.group : 1;
   int64_t off = 0;
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) { a.lvl_off[h] = pl.lvl_off[h]; a.glvl_off[h] = 0; }
   for (int h = 1; h <= pl.H; ++h) {
     a.glvl_off[h] = off;
-    off += (int64_t)pl.B * pl.Hkv * pl.nk * (pl.bk >> (h - 1)) * pl.d;
+    off += (int64_t)pl.B * pl.Hkv * parts * pl.nk * (pl.bk >> (h - 1)) * pl.d;
   }
   const T* q = static_cast<const T*>(Q);
   const T* k = static_cast<const T*>(K);
@@ -322,7 +341,8 @@ static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, con
   const T* vp = static_cast<const T*>(Vp);
   const T* go = static_cast<const T*>(dO);
   const int64_t rows = (int64_t)pl.B * pl.Hq * pl.N;
-  rowdot_kernel<T><<<(unsigned)((rows + 63) / 64), 256, 0, s>>>(go, static_cast<const T*>(O), Dr, rows, pl.d);
+  const int64_t dot_threads = rows * (pl.d / Elem<T>::VEC);
+  rowdot_kernel<T><<<(unsigned)((dot_threads + 255) / 256), 256, 0, s>>>(go, static_cast<const T*>(O), Dr, rows, pl.d);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (use_mfma) {     // bfloat16: dQ and the pooled gradients on the matrix cores
@@ -345,7 +365,7 @@ static hipError_t launch_bwd_t(const Plan& pl, const void* Q, const void* K, con
   const int heads = pl.B * pl.Hkv;
   const int64_t n = (int64_t)heads * pl.N * (pl.d / 4);
   unpool_kernel<T><<<dim3((unsigned)((n + 255) / 256), 2), 256, 0, s>>>(dKp, dVp, static_cast<T*>(dK), static_cast<T*>(dV),
-                                                                         heads, pl.d, a);
+                                                                         heads, parts, pl.d, a);
   return hipGetLastError();
 }
 

@@ -12,10 +12,9 @@
 //        dQ^T += Kbar^T dS^T, whose A operand is read from the row-major Kbar tile with the transposing
 //        LDS load.
 //   bwd_dkv_mfma_kernel  the same with queries and keys exchanged: one workgroup per (32, 64 or 128
-//        adjacent pooled keys of a level, key head); the pooled keys and values sit in registers as B
+//        adjacent pooled keys of a level, query head); the pooled keys and values sit in registers as B
 //        operands (one key per lane), the query blocks that use one of the workgroup's key blocks at this
-//        level (a walk down the level map's columns, for every query head of the group) are staged
-//        through LDS 64 rows at a time; S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and
+//        level (a walk down the level map's columns) are staged through LDS 64 rows at a time; S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and
 //        dKbar^T += Q^T dS with the transposing load on the staged dO and Q.  Half of the wavefronts
 //        accumulate dKbar, the other half dVbar.
 // LDS rows carry 16 bytes of padding, which spreads the rows of an operand read over all banks.
@@ -81,7 +80,8 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(const bf16_t* __res
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, hf = lane >> 5;
   const int slices = (a.bq + 127) / 128;
-  const int i = blockIdx.x / slices, slice = blockIdx.x % slices;
+  // causal rows get longer towards the end of the sequence: the longest are started first
+  const int i = a.causal ? a.nq - 1 - (int)(blockIdx.x / slices) : (int)(blockIdx.x / slices), slice = blockIdx.x % slices;
   const int hq = blockIdx.y, b = blockIdx.z;
   const int hk = hq / (a.Hq / a.Hkv);
   const int64_t qhead = (int64_t)b * a.Hq + hq, khead = (int64_t)b * a.Hkv + hk;
@@ -272,10 +272,13 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(const bf16_t* __res
   }
 }
 
-// One workgroup per (KH * 32 adjacent pooled keys, key head, level).  KH: 32-key tiles of the workgroup
-// (1, 2 or 4).  Blocks of 32 pooled keys or more take KH = keys / 32 (one block per workgroup); smaller
-// blocks are packed G = KH * 32 / keys to a workgroup (at most 16), so that a 32-key matrix tile is full
-// and a query block is staged once for all the blocks of the group that it uses at this level.
+// One workgroup per (KH * 32 adjacent pooled keys, QUERY head, level): the query heads that share a key
+// head each write a partial gradient of their own (added up when the levels are folded back into dK, dV),
+// so that a key block which every query block uses is not one workgroup's walk over the whole group.
+// KH: 32-key tiles of the workgroup (1, 2 or 4).  Blocks of 32 pooled keys or more take KH = keys / 32
+// (one block per workgroup); smaller blocks are packed G = KH * 32 / keys to a workgroup (at most 16),
+// so that a 32-key matrix tile is full and a query block is staged once for all the blocks of the group
+// that it uses at this level.
 // Half of the wavefronts accumulate dKbar (they need S, dP and dS), the other half dVbar (S and P only):
 // that halves the accumulators a wavefront holds, so that two wavefronts fit on each SIMD (two
 // workgroups of four per compute unit, or one of eight for KH = 4) and the matrix pipe works for one
@@ -303,13 +306,13 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
   // next, so that two workgroups on a compute unit do not put both heavier halves on the same SIMDs.
   const int role = (wave / (NW / 2)) ^ (int)(blockIdx.x & 1);
   const int w2 = wave % (NW / 2), kh = w2 % KH, rh = w2 / KH;
-  const int hk = blockIdx.y, b = blockIdx.z;
+  const int hq = blockIdx.y, b = blockIdx.z;
+  const int hk = hq / (a.Hq / a.Hkv);
   const int lg_th = a.lg_bk - (h - 1), span = 1 << (h - 1);
   int G = (KH * 32) >> lg_th;
   G = G < 1 ? 1 : (G > 16 ? 16 : G);
   const int j0 = blockIdx.x * G;
-  const int group = a.Hq / a.Hkv;
-  const int64_t khead = (int64_t)b * a.Hkv + hk;
+  const int64_t qhead = (int64_t)b * a.Hq + hq, khead = (int64_t)b * a.Hkv + hk;
   const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
   const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
 
@@ -347,11 +350,11 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[md][v] = 0.f;
 
-  // First the columns of the level map: which (query head of the group, query block) pairs use any of
-  // the group's key blocks at this level, as an ordered list in LDS with the blocks used as a bit mask
-  // (one round of independent loads per NT entries; a walk that tests one entry after the other spends
-  // a memory latency on each of them).
-  const int E = group * a.nq;
+  // First the columns of the level map: which query blocks of this query head use any of the group's
+  // key blocks at this level, as an ordered list in LDS with the blocks used as a bit mask (one round of
+  // independent loads per NT entries; a walk that tests one entry after the other spends a memory
+  // latency on each of them).
+  const int E = a.nq;
   const int listb = (E * 2 + 15) & ~15;
   uint16_t* kept = reinterpret_cast<uint16_t*>(smem + 2 * BUFB);
   uint16_t* kmask = reinterpret_cast<uint16_t*>(smem + 2 * BUFB + listb);
@@ -361,8 +364,7 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
     const int e = e0 + tid;
     uint32_t bits = 0u;
     if (e < E) {
-      const int64_t qhead = (int64_t)b * a.Hq + hk * group + e / a.nq;
-      const uint8_t* mrow = M + (qhead * a.nq + e % a.nq) * a.nk + j0;
+      const uint8_t* mrow = M + (qhead * a.nq + e) * a.nk + j0;
       for (int g = 0; g < G && j0 + g < a.nk; ++g) bits |= ((int)mrow[g] == h ? 1u : 0u) << g;
     }
     const bool hit = bits != 0u;
@@ -383,16 +385,14 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
     nkept += total;
     __syncthreads();
   }
-  // The stages (a pair on the list, ROWS of the query block's rows) are walked with the NEXT stage's
+  // The stages (a query block on the list, ROWS of its rows) are walked with the NEXT stage's
   // rows already on their way from memory into registers while the current one is multiplied; they go
   // into the other LDS buffer afterwards.
-  struct Stage { int k, gq, i, r0, seg; uint32_t bits; bool ok; };
+  struct Stage { int k, i, r0, seg; uint32_t bits; bool ok; };
   auto settle = [&](Stage st) __attribute__((always_inline)) -> Stage {   // first existing stage at or after (k, r0)
     for (; st.k < nkept; ++st.k, st.r0 = -1) {
-      const int e = (int)kept[st.k];
+      st.i = (int)kept[st.k];
       st.bits = kmask[st.k];
-      st.gq = e / a.nq;
-      st.i = e % a.nq;
       int row_end = (st.i + 1) * a.bq;
       row_end = row_end < a.N ? row_end : a.N;
       if (st.r0 < 0) st.r0 = st.i * a.bq;
@@ -409,7 +409,6 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
   u32x4 qreg[NCH], greg[NCH];
   float lreg = INFINITY, dreg = 0.f;
   auto fetch = [&](const Stage& st) __attribute__((always_inline)) {
-    const int64_t qhead = (int64_t)b * a.Hq + hk * group + st.gq;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       const int x = tid + NT * c, r = x / CPR, ch = x % CPR;
@@ -439,7 +438,7 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
       reinterpret_cast<float*>(base + 2 * TILEB)[ROWS + tid] = dreg;
     }
   };
-  Stage cur = settle(Stage{0, 0, 0, -1, 0, 0u, false});
+  Stage cur = settle(Stage{0, 0, -1, 0, 0u, false});
   if (cur.ok) {
     fetch(cur);
     deposit(0);
@@ -526,7 +525,7 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
         }
     }
     __syncthreads();
-    float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (khead * ((int64_t)a.nk << lg_th) + ((int64_t)j0 << lg_th)) * D;
+    float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (qhead * ((int64_t)a.nk << lg_th) + ((int64_t)j0 << lg_th)) * D;
     const float mul = which ? 1.f : a.scale;
     for (int x = tid; x < KH * 32 * (D / 4); x += NT) {
       const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the group, group of four channels
@@ -541,15 +540,15 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
   }
 }
 
-// two staging buffers + the kept list and block masks of the group's columns (entries: query heads per key
-// head x query blocks) + 8 counters
+// two staging buffers + the kept list and block masks of the group's columns (entries: query blocks) +
+// 8 counters
 size_t bwd_dkv_mfma_smem(int d, int entries) {
   return 2 * (2 * (size_t)64 * (d * 2 + 16) + 2 * 64 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 32;
 }
 
 bool bwd_uses_mfma(const Plan& pl) {
   return pl.dtype == PSA_BF16 && pl.bk >= 8 && pl.bk <= 128 && (pl.d == 64 || pl.d == 128) &&
-         (int64_t)pl.group * pl.nq <= 8192;      // the column's kept list sits in LDS next to the staging buffers
+         pl.nq <= 8192;                          // the column's kept list sits in LDS next to the staging buffers
 }
 
 #ifndef PSA_BWD_SMALL_KH
@@ -567,7 +566,7 @@ static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_
   const int th = pl.bk >> (h - 1);
   int G = KH * 32 / th;                          // key blocks per workgroup, as in the kernel
   G = G < 1 ? 1 : (G > 16 ? 16 : G);
-  kern<<<dim3((pl.nk + G - 1) / G, pl.Hkv, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.group * pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
+  kern<<<dim3((pl.nk + G - 1) / G, pl.Hq, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
                                                                                                   dKp, dVp, h, a);
   return hipGetLastError();
 }
@@ -594,7 +593,7 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
   for (int h = 0; h < PSA_MAX_LEVELS + 2; ++h) { a.lvl_off[h] = pl.lvl_off[h]; a.glvl_off[h] = 0; }
   for (int h = 1; h <= pl.H; ++h) {
     a.glvl_off[h] = off;
-    off += (int64_t)pl.B * pl.Hkv * pl.nk * (pl.bk >> (h - 1)) * pl.d;
+    off += (int64_t)pl.B * pl.Hq * pl.nk * (pl.bk >> (h - 1)) * pl.d;   // one partial tensor per QUERY head
   }
   const bf16_t* q = static_cast<const bf16_t*>(Q);
   const bf16_t* k = static_cast<const bf16_t*>(K);
