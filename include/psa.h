@@ -201,11 +201,12 @@ int psa_attention_fwd(const psa_params* p, const void* Q, const void* K, const v
  *   dO          [B, Hq, N, d], dtype
  *   dQ          out [B, Hq, N, d];  dK, dV  out [B, Hkv, N, d], dtype (every element is written)
  *   scratch     workspace of psa_query_bwd_sizes' scratch_bytes (256-byte aligned): D, block lists, and the
- *               fp32 gradients of the pooled tokens of every level
+ *               fp32 gradients of the pooled tokens of every level (bfloat16 on the matrix cores: one
+ *               partial tensor per query head, added up in a fixed order)
  * bfloat16: the products run on MFMA with fp32 accumulation, P and dS rounded to bfloat16 for the products
  * that consume them (dQ per query block; the pooled dK, dV per key block and level, walking the level
  * map's column).  float32, and bfloat16 shapes the matrix-core kernels do not take (b_k < 8, more than
- * 8192 (query heads per key head x query blocks)): fp32 on the vector unit.  No atomics either way: the
+ * 8192 query blocks): fp32 on the vector unit.  No atomics either way: the
  * result is bit-reproducible.
  * Errors: PSA_EINVAL (null pointer, misaligned scratch), PSA_EUNSUPPORTED (b_k > 128), PSA_ELAUNCH.
  */
