@@ -294,7 +294,7 @@ template <int D, int KH, bool CAUSAL>
 __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
     const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M, const float* __restrict__ lse, const float* __restrict__ Dr,
-    const bf16_t* __restrict__ dO, float* __restrict__ dKp, float* __restrict__ dVp, int h, BwdMfmaArgs a) {
+    const bf16_t* __restrict__ dO, float* __restrict__ dKp, float* __restrict__ dVp, int h_lo, int h_hi, BwdMfmaArgs a) {
   using S = DkvShape<D, KH>;
   constexpr int NW = S::NW, NT = S::NT, RH = S::RH, ROWS = S::ROWS, PITCH = S::PITCH, TILEB = S::TILEB, BUFB = S::BUFB;
   constexpr int CPR = D / 8, KS = D / 16, MD = D / 32;
@@ -308,10 +308,18 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
   const int w2 = wave % (NW / 2), kh = w2 % KH, rh = w2 / KH;
   const int hq = blockIdx.y, b = blockIdx.z;
   const int hk = hq / (a.Hq / a.Hkv);
+  // One launch covers the levels h_lo .. h_hi that share this KH, the coarsest first: its workgroups
+  // walk the longest lists, and the finer levels' shorter ones fill the end of the launch.
+  int h = h_hi, G = 1, bx = blockIdx.x;
+  for (;; --h) {
+    G = (KH * 32) >> (a.lg_bk - (h - 1));
+    G = G < 1 ? 1 : (G > 16 ? 16 : G);
+    const int ng = (a.nk + G - 1) / G;
+    if (bx < ng || h == h_lo) break;
+    bx -= ng;
+  }
   const int lg_th = a.lg_bk - (h - 1), span = 1 << (h - 1);
-  int G = (KH * 32) >> lg_th;
-  G = G < 1 ? 1 : (G > 16 ? 16 : G);
-  const int j0 = blockIdx.x * G;
+  const int j0 = bx * G;
   const int64_t qhead = (int64_t)b * a.Hq + hq, khead = (int64_t)b * a.Hkv + hk;
   const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
   const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
@@ -551,32 +559,33 @@ bool bwd_uses_mfma(const Plan& pl) {
          pl.nq <= 8192;                          // the column's kept list sits in LDS next to the staging buffers
 }
 
-#ifndef PSA_BWD_SMALL_KH
-#define PSA_BWD_SMALL_KH 1
-#endif
-
+// levels h_lo .. h_hi in one launch (they share KH)
 template <int D, int KH, bool CAUSAL>
 static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                                const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
-                               const bf16_t* go, float* dKp, float* dVp, int h, hipStream_t s) {
+                               const bf16_t* go, float* dKp, float* dVp, int h_lo, int h_hi, hipStream_t s) {
   static LdsOptIn optin;
   auto kern = bwd_dkv_mfma_kernel<D, KH, CAUSAL>;
   const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
-  const int th = pl.bk >> (h - 1);
-  int G = KH * 32 / th;                          // key blocks per workgroup, as in the kernel
-  G = G < 1 ? 1 : (G > 16 ? 16 : G);
-  kern<<<dim3((pl.nk + G - 1) / G, pl.Hq, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
-                                                                                                  dKp, dVp, h, a);
+  int groups = 0;
+  for (int h = h_lo; h <= h_hi; ++h) {
+    const int th = pl.bk >> (h - 1);
+    int G = KH * 32 / th;                        // key blocks per workgroup, as in the kernel
+    G = G < 1 ? 1 : (G > 16 ? 16 : G);
+    groups += (pl.nk + G - 1) / G;
+  }
+  kern<<<dim3(groups, pl.Hq, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp,
+                                                                                            h_lo, h_hi, a);
   return hipGetLastError();
 }
 
 template <int D, int KH>
 static hipError_t launch_dkv_c(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                                const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
-                               const bf16_t* go, float* dKp, float* dVp, int h, hipStream_t s) {
-  return pl.causal ? launch_dkv_t<D, KH, true>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s)
-                   : launch_dkv_t<D, KH, false>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+                               const bf16_t* go, float* dKp, float* dVp, int h_lo, int h_hi, hipStream_t s) {
+  return pl.causal ? launch_dkv_t<D, KH, true>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s)
+                   : launch_dkv_t<D, KH, false>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s);
 }
 
 template <int D>
@@ -610,13 +619,19 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
                                                                                  static_cast<bf16_t*>(dQ), a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  for (int h = 1; h <= pl.H; ++h) {
+  auto tiles_of = [&](int h) {                   // KH of level h
     const int th = pl.bk >> (h - 1);
-    if (th > 64) e = launch_dkv_c<D, 4>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
-    else if (th > 32) e = launch_dkv_c<D, 2>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
-    else if (th == 32) e = launch_dkv_c<D, 1>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
-    else e = launch_dkv_c<D, PSA_BWD_SMALL_KH>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, s);
+    return th > 64 ? 4 : (th > 32 ? 2 : 1);
+  };
+  for (int h = 1; h <= pl.H;) {
+    int h_hi = h;
+    while (h_hi < pl.H && tiles_of(h_hi + 1) == tiles_of(h)) ++h_hi;
+    const int kh = tiles_of(h);
+    if (kh == 4) e = launch_dkv_c<D, 4>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, h_hi, s);
+    else if (kh == 2) e = launch_dkv_c<D, 2>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, h_hi, s);
+    else e = launch_dkv_c<D, 1>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h, h_hi, s);
     if (e != hipSuccess) return e;
+    h = h_hi + 1;
   }
   return hipSuccess;
 }
