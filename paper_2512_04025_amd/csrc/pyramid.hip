@@ -10,6 +10,9 @@
 // (sim_h(j), h = 2..H: mean cosine of the token pairs of key block j that lie 2^(h-1) apart): when a
 // workgroup's tokens are whole key blocks it re-reads the K rows it has just streamed (cache hits, no
 // further HBM traffic) and reduces them; other shapes run the same reduction as a kernel of its own.
+// bfloat16 blocks of 32, 64, 96 or 128 tokens with at most five levels take the dots from the matrix cores
+// instead (the band of the block's Gram matrix, one wavefront per block, a kernel of its own behind the
+// pyramid pass).
 // cap_kernel then turns the similarities into the per-block maximum level L.
 #include "psa_dev.h"
 #include "psa_internal.h"
@@ -103,6 +106,98 @@ __device__ void block_sims(const T* __restrict__ khead, int j, int N, int d, int
     double tot = 0.0;
     for (int u = 0; u < 64; ++u) tot += part[u * PSA_MAX_LEVELS + tid];
     out[tid] = npairs > 0 ? (float)(tot / (double)npairs) : 1.f;
+  }
+}
+
+// The same similarities from the matrix cores, by ONE wavefront per key block (bfloat16, b_k a multiple
+// of 32 up to 128, H <= 5 so that a pair is at most 16 tokens apart): the Gram matrix of 32 tokens is one
+// 32x32 accumulator (row tokens as the A operand, column tokens as the B operand, both read straight
+// from memory, 16 bytes per lane and contraction step); a pair (t, t + s) lies either in a diagonal tile
+// or in the tile right of it.  The diagonal gives the norms (through LDS: `nrm`, b_k floats of this
+// wavefront); lane (column n, half hf) holds rows (v/4)*8 + hf*4 + v%4 of a tile in register v and adds
+// the cosines of the pairs it holds; the lanes' sums meet in a butterfly in double (a fixed order).
+template <int D>
+__device__ __forceinline__ void block_sims_mfma(const bf16_t* __restrict__ khead, int j, int N, int bk, int H,
+                                                float* __restrict__ out, float* nrm, int lane) {
+  constexpr int KS = D / 16;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int lo = j * bk;
+  int ntok = N - lo;
+  ntok = ntok > bk ? bk : ntok;
+  // This lane's cosines, by accumulator register: how far apart the two tokens of register v are depends
+  // on the lane and on the kind of tile (diagonal, or right of it) only, so the sums are kept per register
+  // and sorted into levels once at the end.
+  float accd[16], acco[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { accd[v] = 0.f; acco[v] = 0.f; }
+  bf16x8 prev[KS], cur[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) prev[ks] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+  // Cosines of tile `c`, whose rows start at token r_base and whose columns start at token n_base.
+  // Tokens past the end of the sequence are zero rows: their dots and norms are zero, so their "pairs"
+  // add nothing and need no test.
+  auto add_cosines = [&](const f32x16& c, float (&acc)[16], int r_base, int n_base) __attribute__((always_inline)) {
+    const float nn = nrm[n_base + l32];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 nr = *reinterpret_cast<const f32x4*>(nrm + r_base + g * 8 + hf * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[g * 4 + e] += c[g * 4 + e] * __builtin_amdgcn_rcpf(fmaxf(nr[e] * nn, COS_EPS));
+    }
+  };
+  for (int i = 0; i * 32 < bk; ++i) {
+    const int tok = i * 32 + l32;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (tok < ntok) x = *reinterpret_cast<const u32x4*>(khead + (int64_t)(lo + tok) * D + ks * 16 + hf * 8);
+      cur[ks] = __builtin_bit_cast(bf16x8, x);
+    }
+    f32x16 cd, co;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { cd[v] = 0.f; co[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      cd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[ks], cur[ks], cd, 0, 0, 0);
+      co = __builtin_amdgcn_mfma_f32_32x32x16_bf16(prev[ks], cur[ks], co, 0, 0, 0);   // rows: the tile before
+    }
+    // |k_t| from the diagonal: the lane whose rows include its own column
+    float diag = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) diag = (v / 4) * 8 + hf * 4 + v % 4 == l32 ? cd[v] : diag;
+    if (((l32 >> 2) & 1) == hf) nrm[i * 32 + l32] = sqrtf(diag);
+    // the norms pass between lanes of this one wavefront: LDS serves its accesses in order, the fences keep
+    // the compiler from moving the reads above the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    add_cosines(cd, accd, i * 32, i * 32);
+    if (i > 0) add_cosines(co, acco, (i - 1) * 32, i * 32);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) prev[ks] = cur[ks];
+  }
+  // register v: rows (v/4)*8 + hf*4 + v%4, column l32 (32 further in a tile right of the diagonal)
+  float part[4] = {0.f, 0.f, 0.f, 0.f};          // levels 2..5
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int dlt = l32 - ((v / 4) * 8 + hf * 4 + v % 4);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      part[h] += dlt == (2 << h) ? accd[v] : 0.f;
+      part[h] += dlt + 32 == (2 << h) ? acco[v] : 0.f;
+    }
+  }
+  // the lanes' sums meet in double, in a fixed order
+  double sum[4];
+#pragma unroll
+  for (int h = 0; h < 4; ++h) {
+    sum[h] = (double)part[h];
+    for (int o = 1; o < 64; o <<= 1) sum[h] += __shfl_xor(sum[h], o, 64);
+  }
+  if (lane < H - 1) {
+    const int npairs = ntok - (2 << lane);
+    const double tot = lane == 0 ? sum[0] : (lane == 1 ? sum[1] : (lane == 2 ? sum[2] : sum[3]));
+    out[lane] = npairs > 0 ? (float)(tot / (double)npairs) : 1.f;
   }
 }
 
@@ -203,6 +298,11 @@ __global__ __launch_bounds__(256) void pyramid_kernel(const T* __restrict__ K, c
   pyramid_body<T, H>(K, V, Kp, Vp, a, gid);
 }
 
+// the shapes block_sims_mfma takes (its LDS need, 4 * bk floats, is below that of the vector version)
+static bool sims_on_mfma(const Plan& pl) {
+  return pl.dtype == PSA_BF16 && pl.bk % 32 == 0 && pl.bk <= 128 && pl.H <= 5 && (pl.d == 64 || pl.d == 128);
+}
+
 template <typename T>
 static hipError_t launch_sims_t(const Plan& pl, const void* K, float* sims, hipStream_t s);
 
@@ -214,6 +314,18 @@ __global__ __launch_bounds__(256) void sims_kernel(const T* __restrict__ K, floa
   extern __shared__ __attribute__((aligned(16))) unsigned char sim_lds[];
   const int j = blockIdx.x, bh = blockIdx.y;
   block_sims<T>(K + (int64_t)bh * N * d, j, N, d, bk, H, sims + ((int64_t)bh * nk + j) * (H - 1), sim_lds, (int)threadIdx.x);
+}
+
+// The matrix-core reduction as a kernel of its own: four key blocks per workgroup, one per wavefront.
+template <int D>
+__global__ __launch_bounds__(256) void sims_mfma_kernel(const bf16_t* __restrict__ K, float* __restrict__ sims, int N, int bk,
+                                                        int nk, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sim_lds[];
+  const int wave = (int)threadIdx.x >> 6, lane = (int)threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + wave, bh = blockIdx.y;
+  if (j >= nk) return;
+  block_sims_mfma<D>(K + (int64_t)bh * N * D, j, N, bk, H, sims + ((int64_t)bh * nk + j) * (H - 1),
+                     reinterpret_cast<float*>(sim_lds) + wave * bk, lane);
 }
 
 // L_j = max{1, h : sim_h(j) > tau_s^(h)} (Alg. 3: every level is tested).  all_heads: sim_h(j) is first
@@ -246,6 +358,7 @@ static size_t sims_lds_bytes(int bk) {
   return (((size_t)bk * sizeof(float) + 15) & ~(size_t)15) + 64 * PSA_MAX_LEVELS * sizeof(double);
 }
 
+
 template <typename T>
 static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* Kp, void* Vp, float* sims, hipStream_t s) {
   PyrArgs a;
@@ -262,9 +375,12 @@ static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* K
   T* vp = static_cast<T*>(Vp);
   SimArgs sa;
   sa.sims = sims; sa.H = pl.H;
-  // the fused form needs the 256 threads of a workgroup to cover whole key blocks
+  // The fused form needs the 256 threads of a workgroup to cover whole key blocks.  Shapes that the
+  // matrix-core reduction takes run it as a kernel of its own right behind the pyramid pass instead:
+  // inside this kernel it would double the registers of every wavefront and halve the occupancy of the
+  // streaming part (measured: 152 us fused against 76 us + the kernel).
   const int tpb = a.chunks * (pl.bk >> (pl.H - 1));
-  const bool fused = sims && tpb <= 256 && 256 % tpb == 0;
+  const bool fused = sims && !sims_on_mfma(pl) && tpb <= 256 && 256 % tpb == 0;
   const size_t smem = fused ? sims_lds_bytes(pl.bk) : 0;
 #define PSA_PYR_CASE(HH)                                                                              \
   case HH:                                                                                            \
@@ -284,6 +400,14 @@ static hipError_t launch_t(const Plan& pl, const void* K, const void* V, void* K
 template <typename T>
 static hipError_t launch_sims_t(const Plan& pl, const void* K, float* sims, hipStream_t s) {
   const int chunks = pl.d / Elem<T>::VEC;
+  if (sims_on_mfma(pl)) {
+    const bf16_t* k = static_cast<const bf16_t*>(K);
+    const dim3 grid((pl.nk + 3) / 4, pl.B * pl.Hkv);
+    const size_t smem = 4 * (size_t)pl.bk * sizeof(float);
+    if (pl.d == 64) sims_mfma_kernel<64><<<grid, 256, smem, s>>>(k, sims, pl.N, pl.bk, pl.nk, pl.H);
+    else sims_mfma_kernel<128><<<grid, 256, smem, s>>>(k, sims, pl.N, pl.bk, pl.nk, pl.H);
+    return hipGetLastError();
+  }
   sims_kernel<T><<<dim3(pl.nk, pl.B * pl.Hkv), 256, sims_lds_bytes(pl.bk), s>>>(
       static_cast<const T*>(K), sims, pl.N, pl.d, pl.bk, pl.nk, pl.H, chunks);
   return hipGetLastError();
