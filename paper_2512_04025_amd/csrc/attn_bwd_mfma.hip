@@ -17,7 +17,11 @@
 //        level (a walk down the level map's columns) are staged through LDS 64 rows at a time; S = Q Kbar^T and dP = dO Vbar^T, then dVbar^T += dO^T P and
 //        dKbar^T += Q^T dS with the transposing load on the staged dO and Q.  Half of the wavefronts
 //        accumulate dKbar, the other half dVbar.
-// LDS rows carry 16 bytes of padding, which spreads the rows of an operand read over all banks.
+// LDS rows carry padding that spreads the rows of an operand read over the banks: 16 bytes serve the
+// row-wise fragments (eight rows x 16 bytes) at either head dimension and, at d = 64, the transposing
+// load too (four rows x 32 bytes); at d = 128 that load wants the rows 8 banks apart and the fragments
+// an odd multiple of 4, which 48 bytes give (measured: bank conflicts a third, 3 % less time), and 48
+// are used wherever two workgroups still fit a compute unit's LDS.
 #include "psa_dev.h"
 #include "psa_internal.h"
 
@@ -74,7 +78,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(const bf16_t* __res
                                                              const int32_t* __restrict__ cnt, const float* __restrict__ lse,
                                                              const float* __restrict__ Dr, const bf16_t* __restrict__ dO,
                                                              bf16_t* __restrict__ dQ, BwdMfmaArgs a) {
-  constexpr int PITCH = D * 2 + 16, CPR = D / 8, KS = D / 16, MD = D / 32;
+  constexpr int PITCH = D * 2 + (D == 128 ? 48 : 16), CPR = D / 8, KS = D / 16, MD = D / 32;
   constexpr int TILEB = 64 * PITCH, BUFB = 2 * TILEB + 2 * 64 * 4;
   // two buffers, each: Kbar rows [64][PITCH] | Vbar rows [64][PITCH] | bias term [64] | last token [64]
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -284,18 +288,18 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_mfma_kernel(const bf16_t* __res
 // workgroups of four per compute unit, or one of eight for KH = 4) and the matrix pipe works for one
 // while the other is in its exponentials, its LDS reads or a barrier.  Wavefronts of the same half
 // that share a key tile (KH = 1: two of them) split the 32-row chunks of a staged tile.
-template <int D, int KH>
+template <int D, int KH, int PAD>
 struct DkvShape {
   static constexpr int NW = KH == 4 ? 8 : 4, NT = NW * 64, RH = (NW / 2) / KH, ROWS = 64;
-  static constexpr int PITCH = D * 2 + 16, TILEB = ROWS * PITCH, BUFB = 2 * TILEB + 2 * ROWS * (int)sizeof(float);
+  static constexpr int PITCH = D * 2 + PAD, TILEB = ROWS * PITCH, BUFB = 2 * TILEB + 2 * ROWS * (int)sizeof(float);
 };
 
-template <int D, int KH, bool CAUSAL>
-__global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
+template <int D, int KH, bool CAUSAL, int PAD>
+__global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const bf16_t* __restrict__ Kp,
     const bf16_t* __restrict__ Vp, const uint8_t* __restrict__ M, const float* __restrict__ lse, const float* __restrict__ Dr,
     const bf16_t* __restrict__ dO, float* __restrict__ dKp, float* __restrict__ dVp, int h_lo, int h_hi, BwdMfmaArgs a) {
-  using S = DkvShape<D, KH>;
+  using S = DkvShape<D, KH, PAD>;
   constexpr int NW = S::NW, NT = S::NT, RH = S::RH, ROWS = S::ROWS, PITCH = S::PITCH, TILEB = S::TILEB, BUFB = S::BUFB;
   constexpr int CPR = D / 8, KS = D / 16, MD = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -550,8 +554,8 @@ __global__ __launch_bounds__((DkvShape<D, KH>::NT), 2) void bwd_dkv_mfma_kernel(
 
 // two staging buffers + the kept list and block masks of the group's columns (entries: query blocks) +
 // 8 counters
-size_t bwd_dkv_mfma_smem(int d, int entries) {
-  return 2 * (2 * (size_t)64 * (d * 2 + 16) + 2 * 64 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 32;
+size_t bwd_dkv_mfma_smem(int d, int pad, int entries) {
+  return 2 * (2 * (size_t)64 * (d * 2 + pad) + 2 * 64 * sizeof(float)) + 2 * (((size_t)entries * 2 + 15) & ~(size_t)15) + 32;
 }
 
 bool bwd_uses_mfma(const Plan& pl) {
@@ -560,12 +564,12 @@ bool bwd_uses_mfma(const Plan& pl) {
 }
 
 // levels h_lo .. h_hi in one launch (they share KH)
-template <int D, int KH, bool CAUSAL>
+template <int D, int KH, bool CAUSAL, int PAD>
 static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                                const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
                                const bf16_t* go, float* dKp, float* dVp, int h_lo, int h_hi, hipStream_t s) {
   static LdsOptIn optin;
-  auto kern = bwd_dkv_mfma_kernel<D, KH, CAUSAL>;
+  auto kern = bwd_dkv_mfma_kernel<D, KH, CAUSAL, PAD>;
   const hipError_t e = allow_max_lds(reinterpret_cast<const void*>(kern), &optin);
   if (e != hipSuccess) return e;
   int groups = 0;
@@ -575,8 +579,8 @@ static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_
     G = G < 1 ? 1 : (G > 16 ? 16 : G);
     groups += (pl.nk + G - 1) / G;
   }
-  kern<<<dim3(groups, pl.Hq, pl.B), DkvShape<D, KH>::NT, bwd_dkv_mfma_smem(D, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp,
-                                                                                            h_lo, h_hi, a);
+  kern<<<dim3(groups, pl.Hq, pl.B), DkvShape<D, KH, PAD>::NT, bwd_dkv_mfma_smem(D, PAD, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
+                                                                                                    dKp, dVp, h_lo, h_hi, a);
   return hipGetLastError();
 }
 
@@ -584,8 +588,12 @@ template <int D, int KH>
 static hipError_t launch_dkv_c(const Plan& pl, const BwdMfmaArgs& a, const bf16_t* q, const bf16_t* k, const bf16_t* v,
                                const bf16_t* kp, const bf16_t* vp, const uint8_t* M, const float* lse, const float* Dr,
                                const bf16_t* go, float* dKp, float* dVp, int h_lo, int h_hi, hipStream_t s) {
-  return pl.causal ? launch_dkv_t<D, KH, true>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s)
-                   : launch_dkv_t<D, KH, false>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s);
+  // the wider padding where two workgroups of it still share a compute unit (d = 128 only: see the header)
+  if (D == 128 && 2 * bwd_dkv_mfma_smem(D, 48, pl.nq) <= LDS_LIMIT)
+    return pl.causal ? launch_dkv_t<D, KH, true, D == 128 ? 48 : 16>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s)
+                     : launch_dkv_t<D, KH, false, D == 128 ? 48 : 16>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s);
+  return pl.causal ? launch_dkv_t<D, KH, true, 16>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s)
+                   : launch_dkv_t<D, KH, false, 16>(pl, a, q, k, v, kp, vp, M, lse, Dr, go, dKp, dVp, h_lo, h_hi, s);
 }
 
 template <int D>
@@ -614,7 +622,7 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
   static LdsOptIn dq_optin;
   hipError_t e = allow_max_lds(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<D>), &dq_optin);
   if (e != hipSuccess) return e;
-  constexpr size_t dq_smem = 2 * (2 * (size_t)64 * (D * 2 + 16) + 2 * 64 * 4);   // two buffers of the kernel's layout
+  constexpr size_t dq_smem = 2 * (2 * (size_t)64 * (D * 2 + (D == 128 ? 48 : 16)) + 2 * 64 * 4);   // two buffers of the kernel's layout
   bwd_dq_mfma_kernel<D><<<dim3(pl.nq * slices, pl.Hq, pl.B), 256, dq_smem, s>>>(q, k, v, kp, vp, idx, cnt, lse, Dr, go,
                                                                                  static_cast<bf16_t*>(dQ), a);
   e = hipGetLastError();
