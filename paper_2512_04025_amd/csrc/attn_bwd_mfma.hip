@@ -403,8 +403,8 @@ __global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_ke
   struct Stage { int k, i, r0, seg; uint32_t bits; bool ok; };
   auto settle = [&](Stage st) __attribute__((always_inline)) -> Stage {   // first existing stage at or after (k, r0)
     for (; st.k < nkept; ++st.k, st.r0 = -1) {
-      st.i = (int)kept[st.k];
-      st.bits = kmask[st.k];
+      st.i = __builtin_amdgcn_readfirstlane((int)kept[st.k]);       // the same for every lane: scalar from here on
+      st.bits = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmask[st.k]);
       int row_end = (st.i + 1) * a.bq;
       row_end = row_end < a.N ? row_end : a.N;
       if (st.r0 < 0) st.r0 = st.i * a.bq;
@@ -421,20 +421,37 @@ __global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_ke
   u32x4 qreg[NCH], greg[NCH];
   float lreg = INFINITY, dreg = 0.f;
   auto fetch = [&](const Stage& st) __attribute__((always_inline)) {
+    // a scalar base for the stage plus this thread's fixed 32-bit offsets: no 64-bit vector arithmetic
+    const int64_t row0 = qhead * a.N + st.r0;
+    const bf16_t* qs = Q + row0 * D;
+    const bf16_t* gs = dO + row0 * D;
+    if (st.seg == ROWS) {                          // all but a ragged last query block
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      const int x = tid + NT * c, r = x / CPR, ch = x % CPR;
-      const u32x4 z = {0u, 0u, 0u, 0u};
-      qreg[c] = z;
-      greg[c] = z;
-      if (r < st.seg) {
-        qreg[c] = *reinterpret_cast<const u32x4*>(Q + (qhead * a.N + st.r0 + r) * D + ch * 8);
-        greg[c] = *reinterpret_cast<const u32x4*>(dO + (qhead * a.N + st.r0 + r) * D + ch * 8);
+      for (int c = 0; c < NCH; ++c) {
+        const int x = tid + NT * c, off = (x / CPR) * D + (x % CPR) * 8;
+        qreg[c] = *reinterpret_cast<const u32x4*>(qs + off);
+        greg[c] = *reinterpret_cast<const u32x4*>(gs + off);
       }
-    }
-    if (tid < ROWS) {
-      lreg = tid < st.seg ? lse[qhead * a.N + st.r0 + tid] * LOG2E : INFINITY;
-      dreg = tid < st.seg ? Dr[qhead * a.N + st.r0 + tid] : 0.f;
+      if (tid < ROWS) {
+        lreg = lse[row0 + tid] * LOG2E;
+        dreg = Dr[row0 + tid];
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int x = tid + NT * c, r = x / CPR, off = r * D + (x % CPR) * 8;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        qreg[c] = z;
+        greg[c] = z;
+        if (r < st.seg) {
+          qreg[c] = *reinterpret_cast<const u32x4*>(qs + off);
+          greg[c] = *reinterpret_cast<const u32x4*>(gs + off);
+        }
+      }
+      if (tid < ROWS) {
+        lreg = tid < st.seg ? lse[row0 + tid] * LOG2E : INFINITY;
+        dreg = tid < st.seg ? Dr[row0 + tid] : 0.f;
+      }
     }
   };
   auto deposit = [&](int buf) __attribute__((always_inline)) {
