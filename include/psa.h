@@ -124,9 +124,11 @@ int psa_permute_tokens(const psa_params* p, int32_t heads, const void* X, const 
  *   sim     out, float [B, Hkv, nk, H-1]: the per-head similarities (NULL allowed only when H = 1)
  *   L       out, uint8 [B, Hkv, nk], values 1..H
  * psa_level_cap reads K once.  psa_build_pyramid_cap is psa_build_pyramid that also produces sim and L in
- * the same pass over K: when the keys of a block are handled by one workgroup of the pooling kernel
- * (16-byte chunks per row x b_k / 2^(H-1) divides 256: every benchmark shape) the block's rows are
- * reduced right after they were streamed, from cache; other shapes run the reduction as a second kernel.
+ * the same call.  bfloat16 with b_k a multiple of 32 up to 128 and H <= 5: the dots come from the matrix
+ * cores, one wavefront per key block, in a kernel right behind the pooling pass.  Otherwise, when the
+ * keys of a block are handled by one workgroup of the pooling kernel (16-byte chunks per row x
+ * b_k / 2^(H-1) divides 256) the block's rows are reduced inside it right after they were streamed, from
+ * cache; the remaining shapes run the vector-unit reduction as a second kernel.
  * Arithmetic: dot products and norms in fp32, the mean in fp64 in a fixed order (deterministic).
  * Errors: PSA_EINVAL (null pointer, threshold outside [-1, 1], unknown reduce), PSA_EUNSUPPORTED
  *         (b_k > 8192), PSA_ELAUNCH.
