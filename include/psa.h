@@ -129,7 +129,8 @@ int psa_permute_tokens(const psa_params* p, int32_t heads, const void* X, const 
  * keys of a block are handled by one workgroup of the pooling kernel (16-byte chunks per row x
  * b_k / 2^(H-1) divides 256) the block's rows are reduced inside it right after they were streamed, from
  * cache; the remaining shapes run the vector-unit reduction as a second kernel.
- * Arithmetic: dot products and norms in fp32, the mean in fp64 in a fixed order (deterministic).
+ * Arithmetic: dot products and norms in fp32; the cosines are added in a fixed order (deterministic), in
+ * fp64 (on the matrix-core path: at most a dozen per lane in fp32, then the lanes' sums in fp64).
  * Errors: PSA_EINVAL (null pointer, threshold outside [-1, 1], unknown reduce), PSA_EUNSUPPORTED
  *         (b_k > 8192), PSA_ELAUNCH.
  */
