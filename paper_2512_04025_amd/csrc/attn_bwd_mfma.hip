@@ -314,22 +314,26 @@ __global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_ke
   const int hk = hq / (a.Hq / a.Hkv);
   // One launch covers the levels h_lo .. h_hi that share this KH, the coarsest first: its workgroups
   // walk the longest lists, and the finer levels' shorter ones fill the end of the launch.
-  int h = h_hi, G = 1, bx = blockIdx.x;
+  // A block of more pooled keys than the workgroup takes (KH * 32) is shared by several workgroups,
+  // `pieces` of them, each with its own KH * 32 keys (and its own walk down the same column).
+  int h = h_hi, G = 1, pieces = 1, bx = blockIdx.x;
   for (;; --h) {
-    G = (KH * 32) >> (a.lg_bk - (h - 1));
+    const int lg = a.lg_bk - (h - 1);
+    G = (KH * 32) >> lg;
     G = G < 1 ? 1 : (G > 16 ? 16 : G);
-    const int ng = (a.nk + G - 1) / G;
+    pieces = (1 << lg) > KH * 32 ? (1 << lg) / (KH * 32) : 1;
+    const int ng = pieces * ((a.nk + G - 1) / G);
     if (bx < ng || h == h_lo) break;
     bx -= ng;
   }
   const int lg_th = a.lg_bk - (h - 1), span = 1 << (h - 1);
-  const int j0 = bx * G;
+  const int j0 = (bx / pieces) * G, koff = (bx % pieces) * KH * 32;   // first block; first key inside it
   const int64_t qhead = (int64_t)b * a.Hq + hq, khead = (int64_t)b * a.Hkv + hk;
   const bf16_t* kbase = h == 1 ? K + khead * (int64_t)a.N * D : Kp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
   const bf16_t* vbase = h == 1 ? V + khead * (int64_t)a.N * D : Vp + a.lvl_off[h] + khead * ((int64_t)a.nk << lg_th) * D;
 
-  // this lane's pooled key (B operands of both first products): key kh*32 + l32 of the group
-  const int key = kh * 32 + l32;
+  // this lane's pooled key (B operands of both first products): key koff + kh*32 + l32 of the group
+  const int key = koff + kh * 32 + l32;
   const int kblk = key >> lg_th;                  // its block within the group
   const int prow = (j0 << lg_th) + key;
   const int first = prow * span;
@@ -339,7 +343,7 @@ __global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_ke
   const float bias2 = valid ? __log2f((float)ctok) : -INFINITY;
   const int last = first + (ctok > 0 ? ctok : 1) - 1;
   // the blocks this wavefront's 32 keys belong to, as bits of a stage's block mask
-  const int wb0 = (kh * 32) >> lg_th, wb1 = (kh * 32 + 31) >> lg_th;
+  const int wb0 = (koff + kh * 32) >> lg_th, wb1 = (koff + kh * 32 + 31) >> lg_th;
   const uint32_t wave_bits = wb0 < G ? (((2u << (wb1 < G ? wb1 : G - 1)) - 1u) & ~((1u << wb0) - 1u)) : 0u;
   bf16x8 kf[KS], vf[KS];                          // vf: only the dKbar half multiplies by it
 #pragma unroll
@@ -557,14 +561,14 @@ __global__ __launch_bounds__((DkvShape<D, KH, PAD>::NT), 2) void bwd_dkv_mfma_ke
     float* dst = (which ? dVp : dKp) + a.glvl_off[h] + (qhead * ((int64_t)a.nk << lg_th) + ((int64_t)j0 << lg_th)) * D;
     const float mul = which ? 1.f : a.scale;
     for (int x = tid; x < KH * 32 * (D / 4); x += NT) {
-      const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the group, group of four channels
-      const int blk = kk >> lg_th;
+      const int kk = x / (D / 4), c4 = x % (D / 4);     // key of the workgroup, group of four channels
+      const int blk = (koff + kk) >> lg_th;
       if (blk >= G || j0 + blk >= a.nk) continue;
       const int g2 = kk / 32, k32 = kk % 32;
       f32x4 sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int r = 0; r < RH; ++r) sum += *reinterpret_cast<const f32x4*>(red + (((r * KH + g2) * 32 + k32) * D + c4 * 4));
-      *reinterpret_cast<f32x4*>(dst + (int64_t)kk * D + c4 * 4) = sum * mul;
+      *reinterpret_cast<f32x4*>(dst + (int64_t)(koff + kk) * D + c4 * 4) = sum * mul;
     }
   }
 }
@@ -594,7 +598,8 @@ static hipError_t launch_dkv_t(const Plan& pl, const BwdMfmaArgs& a, const bf16_
     const int th = pl.bk >> (h - 1);
     int G = KH * 32 / th;                        // key blocks per workgroup, as in the kernel
     G = G < 1 ? 1 : (G > 16 ? 16 : G);
-    groups += (pl.nk + G - 1) / G;
+    const int pieces = th > KH * 32 ? th / (KH * 32) : 1;
+    groups += pieces * ((pl.nk + G - 1) / G);
   }
   kern<<<dim3(groups, pl.Hq, pl.B), DkvShape<D, KH, PAD>::NT, bwd_dkv_mfma_smem(D, PAD, pl.nq), s>>>(q, k, v, kp, vp, M, lse, Dr, go,
                                                                                                     dKp, dVp, h_lo, h_hi, a);
@@ -644,8 +649,12 @@ static hipError_t launch_bwd_mfma_t(const Plan& pl, const void* Q, const void* K
                                                                                  static_cast<bf16_t*>(dQ), a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  auto tiles_of = [&](int h) {                   // KH of level h
+  // KH of level h.  d = 64: a 128-key block goes to two workgroups of 64 keys (four wavefronts, three of
+  // them per SIMD) rather than one of eight wavefronts that would have a compute unit to itself: 83 -> 55 ms
+  // at the 131072-token shape, although both then stage the block's query rows.
+  auto tiles_of = [&](int h) {
     const int th = pl.bk >> (h - 1);
+    if (D == 64 && th > 64) return 2;
     return th > 64 ? 4 : (th > 32 ? 2 : 1);
   };
   for (int h = 1; h <= pl.H;) {
