@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--levels", type=int, default=None, help="pyramid depth override (1 = binary block-sparse)")
     ap.add_argument("--seq", type=int, default=None, help="sequence length override (shorter variant of the workload)")
     ap.add_argument("--heads", type=int, default=None, help="query-head count override (KV heads scale along)")
+    ap.add_argument("--bq", type=int, default=None, help="query block size override (block-size ablation, App. C)")
+    ap.add_argument("--bk", type=int, default=None, help="key block size override (a power of two)")
     ap.add_argument("--copy-probe-mb", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-attainable", action="store_true", help="skip the copy / MFMA-only microbenchmarks")
@@ -246,7 +248,9 @@ def main():
     w = si.CONFIGS[args.workload]
     # the importance estimator of the workload (8 pooled representatives per block) stays the same when
     # the pyramid depth is overridden, so --levels 1 is block-sparse attention on the SAME scores
-    sq, sk = 8, w.bk >> (w.levels - 1)
+    if args.bq or args.bk:
+        w = w.with_(bq=args.bq or w.bq, bk=args.bk or w.bk)
+    sq, sk = 8, (w.bk >> (w.levels - 1) if not (args.bq or args.bk) else min(8, w.bk))
     if args.levels:
         w = w.with_(levels=args.levels)
     if args.seq or args.heads:
